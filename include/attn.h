@@ -1,0 +1,84 @@
+/*
+ * attn.h -- C ABI of the MI355X (gfx950) flash-attention forward library.
+ *
+ * Operation (paper Section 2, "standard attention": S = Q K^T, P = softmax(S)
+ * row-wise, O = P V, computed tile by tile with an online softmax so that S is
+ * never materialised; Figure 1 gives the tiled kernel this library re-designs
+ * for CDNA4):
+ *
+ *     s_ij   = scale * sum_d Q[b,h,i,d] * K[b,hk,j,d]        hk = h / (Hq/Hkv)
+ *     J(i)   = { j in [0,Sk) : !causal  or  j <= i + (Sk - Sq) }
+ *     lse_i  = ln sum_{j in J(i)} exp(s_ij)
+ *     O[b,h,i,:] = sum_{j in J(i)} exp(s_ij - lse_i) * V[b,hk,j,:]
+ *
+ * The paper's definition carries no scale; the workload it evaluates is causal
+ * grouped-query attention in bf16 with fp32 accumulation (Section 8, Figure 1:
+ * kv head = q head / gqa).  Scores, running max / sum and the output
+ * accumulator are fp32; only P is rounded to bf16 (as the second MFMA operand)
+ * and O is rounded once, to nearest even, when stored.
+ *
+ * All pointers are DEVICE pointers into caller-owned memory; the library
+ * neither allocates nor frees nor synchronises.  Tensors are contiguous and
+ * row-major:
+ *     q   : bf16 [B, Hq,  Sq, D]
+ *     k,v : bf16 [B, Hkv, Sk, D]
+ *     o   : bf16 [B, Hq,  Sq, D]     (written)
+ *     lse : fp32 [B, Hq,  Sq]        (written; may be NULL -> not written)
+ * q, k, v, o must be 16-byte aligned, lse 4-byte aligned.  o/lse must not alias
+ * the inputs.  A query row with no visible key (causal and Sq > Sk only) gets
+ * O = 0 and lse = -inf.
+ *
+ * Supported: D in {64, 128}; any B, Hq, Hkv, Sq, Sk >= 1 with Hq % Hkv == 0 and
+ * B*Hq*ceil(Sq/128) < 2^31; scale finite and > 0.
+ *
+ * `stream` is a hipStream_t passed as void* (NULL = the default stream).  The
+ * call enqueues the kernel on that stream and returns; the result is ready
+ * when the stream reaches that point.  Thread-safe, no global state.
+ *
+ * Every argument check happens before the first HIP call, so error paths can be
+ * exercised on a machine without a GPU.  Nothing is ever silently wrong: an
+ * unsupported request returns an error and launches nothing.
+ */
+#ifndef ATTN_MI355X_H
+#define ATTN_MI355X_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ATTN_OK              =  0,
+    ATTN_ERR_NULL_PTR    = -1,  /* q, k, v or o is NULL                               */
+    ATTN_ERR_BAD_SHAPE   = -2,  /* a dimension <= 0, Hq % Hkv != 0, or grid overflow  */
+    ATTN_ERR_UNSUPPORTED = -3,  /* D not in {64,128}                                  */
+    ATTN_ERR_MISALIGNED  = -4,  /* q/k/v/o not 16-byte aligned, lse not 4-byte aligned */
+    ATTN_ERR_BAD_SCALE   = -5,  /* scale is NaN, infinite, zero or negative           */
+    ATTN_ERR_LAUNCH      = -6   /* the HIP runtime refused the launch                 */
+};
+
+/*
+ * Flash-attention forward (Section 2 definition; Figure 1 tiling; Section 8
+ * causal GQA workload).  Returns ATTN_OK or a negative ATTN_ERR_* code.
+ * causal: 0 = all keys visible, non-zero = bottom-right aligned causal mask.
+ */
+int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
+             int B, int Hq, int Hkv, int Sq, int Sk, int D,
+             int causal, float scale, void *stream);
+
+/* Static, never-freed description of a return code of this library. */
+const char *attn_strerror(int code);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int attn_version(void);
+
+/*
+ * Algorithmic FLOPs of one attn_fwd call: 4*D per visible (query, key) pair
+ * (2*D for q.k and 2*D for p.v; softmax and masked pairs are not counted).
+ * Host-only arithmetic, no GPU needed.  Returns -1 on bad dimensions.
+ */
+double attn_fwd_flops(int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTN_MI355X_H */

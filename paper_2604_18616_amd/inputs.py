@@ -1,0 +1,135 @@
+"""Seeded synthetic inputs for the attention-forward workloads.
+
+This module holds no attention arithmetic: it only produces the Q/K/V bit
+patterns (and sampled query-row lists) that both the HIP path and the CPU
+reference are fed, so that the two always see identical bits.
+
+Recipe: a splitmix64 counter stream -> two 32-bit uniforms per draw ->
+Box-Muller normal in fp64 -> scale by sigma (+ optional shift) -> fp32 -> bf16
+round-to-nearest-even.  Draw order per workload: Q, K, V, then the per-head key
+shift if the workload has one.  Values and shapes mirror the paper's attention
+workload (Section 8: bf16, causal GQA prefill shapes, synthetic N(0,1) data).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+_M64 = (1 << 64) - 1
+
+
+def splitmix64(counter: np.ndarray, seed: int) -> np.ndarray:
+    """splitmix64 output for state = seed + (counter+1)*golden-gamma (vectorised, uint64)."""
+    with np.errstate(over="ignore"):
+        z = (counter.astype(np.uint64) + np.uint64(1)) * np.uint64(0x9E3779B97F4A7C15) + np.uint64(seed & _M64)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        return z ^ (z >> np.uint64(31))
+
+
+def normal_stream(seed: int, start: int, n: int) -> np.ndarray:
+    """n iid N(0,1) draws (fp64) at stream positions start .. start+n-1."""
+    out = np.empty(n, dtype=np.float64)
+    chunk = 1 << 22
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        r = splitmix64(np.arange(start + lo, start + hi, dtype=np.uint64), seed)
+        u1 = ((r >> np.uint64(32)).astype(np.float64) + 1.0) * (1.0 / 4294967296.0)   # (0, 1]
+        u2 = (r & np.uint64(0xFFFFFFFF)).astype(np.float64) * (1.0 / 4294967296.0)    # [0, 1)
+        out[lo:hi] = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    return out
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns (uint16), round to nearest even.  Finite inputs only."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    u = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (u >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(h: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns (uint16) -> fp32 (exact)."""
+    return (np.ascontiguousarray(h, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    B: int
+    Hq: int
+    Hkv: int
+    Sq: int
+    Sk: int
+    D: int
+    causal: bool
+    seed: int
+    sigma: float = 1.0
+    k_shift: bool = False          # add one N(0,1) constant per kv head to K before rounding
+    check_rows: int = 0            # 0 = every row is cheap enough to check; else rows per head
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / float(np.sqrt(self.D))
+
+    def flops(self) -> float:
+        """Algorithmic FLOPs: 4*D per visible (query, key) pair."""
+        if not self.causal:
+            pairs = self.Sq * self.Sk
+        else:
+            i = np.arange(self.Sq, dtype=np.int64)
+            pairs = int(np.clip(i + (self.Sk - self.Sq) + 1, 0, self.Sk).sum())
+        return 4.0 * self.D * self.B * self.Hq * pairs
+
+    def dense_flops(self) -> float:
+        """The paper's 'effective' convention (Section 8.2): dense FLOPs incl. masked pairs."""
+        return 4.0 * self.D * self.B * self.Hq * self.Sq * self.Sk
+
+    def bytes(self) -> float:
+        """Compulsory HBM bytes: Q, O (bf16), K, V (bf16), LSE (fp32)."""
+        return (2 * self.B * self.Hq * self.Sq * self.D * 2 + 2 * self.B * self.Hkv * self.Sk * self.D * 2
+                + 4 * self.B * self.Hq * self.Sq)
+
+
+# The five benchmark configurations, in the order the baseline file lists them.
+WORKLOADS = {
+    "C1": Workload("C1", 1, 2, 2, 128, 128, 64, False, 1001),
+    "C2": Workload("C2", 16, 16, 16, 1024, 1024, 128, False, 1002, check_rows=64),
+    "C3": Workload("C3", 4, 32, 8, 4096, 4096, 128, True, 1003, check_rows=64),
+    "C4": Workload("C4", 2, 16, 16, 8192, 8192, 64, False, 1004, sigma=0.5, k_shift=True, check_rows=512),
+    "C5": Workload("C5", 1, 32, 8, 32768, 32768, 128, True, 1005, check_rows=256),
+}
+
+
+def make_qkv(w: Workload):
+    """Q [B,Hq,Sq,D], K, V [B,Hkv,Sk,D] as uint16 arrays of bf16 bit patterns."""
+    nq = w.B * w.Hq * w.Sq * w.D
+    nk = w.B * w.Hkv * w.Sk * w.D
+    q = (normal_stream(w.seed, 0, nq) * w.sigma).astype(np.float32)
+    k = (normal_stream(w.seed, nq, nk) * w.sigma).astype(np.float32)
+    v = (normal_stream(w.seed, nq + nk, nk) * w.sigma).astype(np.float32)
+    k = k.reshape(w.B, w.Hkv, w.Sk, w.D)
+    if w.k_shift:
+        c = normal_stream(w.seed, nq + 2 * nk, w.Hkv).astype(np.float32)
+        k = k + c.reshape(1, w.Hkv, 1, 1)
+    return (f32_to_bf16_bits(q).reshape(w.B, w.Hq, w.Sq, w.D),
+            f32_to_bf16_bits(k).reshape(w.B, w.Hkv, w.Sk, w.D),
+            f32_to_bf16_bits(v).reshape(w.B, w.Hkv, w.Sk, w.D))
+
+
+def sample_rows(w: Workload, n: int) -> np.ndarray:
+    """Query rows to check per (b, h): int32 [B*Hq, n], sorted.
+
+    Always contains the tile-edge / causal-extreme rows {0,1,63,64,127,128,255,256,
+    Sq-2,Sq-1} that exist; the rest is drawn without replacement from a splitmix64
+    stream seeded with seed ^ (b*Hq + h).
+    """
+    n = min(n, w.Sq)
+    forced = sorted({r for r in (0, 1, 63, 64, 127, 128, 255, 256, w.Sq - 2, w.Sq - 1) if 0 <= r < w.Sq})[:n]
+    out = np.empty((w.B * w.Hq, n), dtype=np.int32)
+    for bh in range(w.B * w.Hq):
+        keys = splitmix64(np.arange(w.Sq, dtype=np.uint64), (w.seed ^ bh) + 0x5EED)
+        keys[np.asarray(forced, dtype=np.int64)] = 0          # forced rows sort first
+        order = np.argsort(keys, kind="stable")
+        out[bh] = np.sort(order[:n])
+    return out

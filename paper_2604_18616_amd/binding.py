@@ -1,0 +1,93 @@
+"""ctypes binding of the C-ABI attention library (argument marshalling only).
+
+Function names mirror include/attn.h.  Tensors are torch CUDA tensors (PyTorch is
+used for device memory and streams only); their device pointers and the current
+stream handle are passed straight to the library.  There is no fallback: if the
+HIP library is missing or fails, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from .build import LIB_PATH, build_library
+
+_lib = None
+
+
+class AttnError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("attn_fwd failed (%d): %s" % (code, msg))
+        self.code = code
+
+
+def load_library(build_if_missing: bool = True):
+    """Load libattn_mi355x.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            if not build_if_missing:
+                raise FileNotFoundError(LIB_PATH)
+            build_library()
+        lib = ctypes.CDLL(LIB_PATH)
+        i, f, p = ctypes.c_int, ctypes.c_float, ctypes.c_void_p
+        lib.attn_fwd.restype = i
+        lib.attn_fwd.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, f, p]
+        lib.attn_strerror.restype = ctypes.c_char_p
+        lib.attn_strerror.argtypes = [i]
+        lib.attn_version.restype = i
+        lib.attn_version.argtypes = []
+        lib.attn_fwd_flops.restype = ctypes.c_double
+        lib.attn_fwd_flops.argtypes = [i, i, i, i, i, i, i]
+        _lib = lib
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return load_library().attn_strerror(int(code)).decode()
+
+
+def version() -> int:
+    return load_library().attn_version()
+
+
+def attn_fwd_flops(B, Hq, Hkv, Sq, Sk, D, causal) -> float:
+    return load_library().attn_fwd_flops(B, Hq, Hkv, Sq, Sk, D, int(bool(causal)))
+
+
+def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, causal, scale, stream_ptr) -> int:
+    """Direct call with integer device addresses; returns the library's status code."""
+    return load_library().attn_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D,
+                                   int(bool(causal)), float(scale), stream_ptr)
+
+
+def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
+    """O, LSE = attention forward of bf16 CUDA tensors q [B,Hq,Sq,D], k/v [B,Hkv,Sk,D].
+
+    o (bf16 [B,Hq,Sq,D]) and lse (fp32 [B,Hq,Sq]) are allocated with torch if not given.
+    The kernel is enqueued on `stream` (default: torch's current stream); no sync.
+    """
+    import torch
+
+    if not (q.is_cuda and k.is_cuda and v.is_cuda):
+        raise ValueError("q, k, v must be CUDA tensors: there is no CPU path")
+    for t in (q, k, v):
+        if t.dtype != torch.bfloat16 or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError("q, k, v must be contiguous 4-D bfloat16 tensors")
+    B, Hq, Sq, D = q.shape
+    Bk, Hkv, Sk, Dk = k.shape
+    if v.shape != k.shape or Bk != B or Dk != D:
+        raise ValueError("inconsistent q/k/v shapes")
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, Hq, Sq), dtype=torch.float32, device=q.device)
+    if scale is None:
+        scale = float(D) ** -0.5
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    rc = attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                      B, Hq, Hkv, Sq, Sk, D, causal, scale, stream.cuda_stream)
+    if rc != 0:
+        raise AttnError(rc, strerror(rc))
+    return o, lse

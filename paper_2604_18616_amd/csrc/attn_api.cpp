@@ -1,0 +1,70 @@
+// C ABI of the attention-forward library: argument validation and dispatch.
+// Every check below runs before the first HIP call, so the error paths work on a
+// machine without a GPU.  See include/attn.h for the contract.
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/attn.h"
+#include "attn_launch.h"
+
+#define ATTN_VERSION 100   /* 0.1.0 */
+
+static int check_dims(int B, int Hq, int Hkv, int Sq, int Sk, int D) {
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Sq <= 0 || Sk <= 0 || D <= 0) return ATTN_ERR_BAD_SHAPE;
+    if (Hq % Hkv != 0) return ATTN_ERR_BAD_SHAPE;
+    return ATTN_OK;
+}
+
+extern "C" int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                        int B, int Hq, int Hkv, int Sq, int Sk, int D,
+                        int causal, float scale, void* stream) {
+    if (!q || !k || !v || !o) return ATTN_ERR_NULL_PTR;
+    if (int rc = check_dims(B, Hq, Hkv, Sq, Sk, D)) return rc;
+    if (D != 64 && D != 128) return ATTN_ERR_UNSUPPORTED;
+    const long long nQt = ((long long)Sq + 127) / 128;
+    const long long nblocks = (long long)B * Hq * nQt;
+    if (nblocks >= (1LL << 31)) return ATTN_ERR_BAD_SHAPE;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15u) return ATTN_ERR_MISALIGNED;
+    if (lse && ((uintptr_t)lse & 3u)) return ATTN_ERR_MISALIGNED;
+    if (!(scale > 0.0f) || isinf(scale)) return ATTN_ERR_BAD_SCALE;   // rejects NaN, <= 0, inf
+
+    AttnParams p;
+    p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v;
+    p.o = (__bf16*)o; p.lse = lse;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.Sq = Sq; p.Sk = Sk;
+    p.nQt = (int)nQt; p.nblocks = (int)nblocks;
+    p.scale = scale;
+    p.scale_log2 = (float)((double)scale * 1.4426950408889634074);
+    return attn_launch(p, D, causal != 0, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" const char* attn_strerror(int code) {
+    switch (code) {
+        case ATTN_OK:              return "success";
+        case ATTN_ERR_NULL_PTR:    return "q, k, v or o is NULL";
+        case ATTN_ERR_BAD_SHAPE:   return "bad shape: a dimension is <= 0, Hq is not a multiple of Hkv, or the grid overflows";
+        case ATTN_ERR_UNSUPPORTED: return "unsupported head dimension (D must be 64 or 128)";
+        case ATTN_ERR_MISALIGNED:  return "misaligned pointer (q/k/v/o need 16 bytes, lse 4 bytes)";
+        case ATTN_ERR_BAD_SCALE:   return "scale must be finite and > 0";
+        case ATTN_ERR_LAUNCH:      return "the HIP runtime refused the kernel launch";
+        default:                   return "unknown attn error code";
+    }
+}
+
+extern "C" int attn_version(void) { return ATTN_VERSION; }
+
+extern "C" double attn_fwd_flops(int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal) {
+    if (check_dims(B, Hq, Hkv, Sq, Sk, D)) return -1.0;
+    double pairs = 0.0;
+    if (!causal) {
+        pairs = (double)Sq * (double)Sk;
+    } else {
+        for (int i = 0; i < Sq; ++i) {
+            long long n = (long long)i + (Sk - Sq) + 1;
+            if (n < 0) n = 0;
+            if (n > Sk) n = Sk;
+            pairs += (double)n;
+        }
+    }
+    return 4.0 * D * (double)B * (double)Hq * pairs;
+}

@@ -1,0 +1,21 @@
+// Internal interface between the C-ABI translation unit (argument checks, no device
+// code) and the kernel translation unit.
+#pragma once
+#include <hip/hip_runtime.h>
+
+struct AttnParams {
+    const __bf16* q;
+    const __bf16* k;
+    const __bf16* v;
+    __bf16* o;
+    float* lse;        // may be null
+    int B, Hq, Hkv, Sq, Sk;
+    int nQt;           // query tiles of 128 rows per head
+    int nblocks;       // B * Hq * nQt
+    float scale;       // multiplier on q.k before the softmax
+    float scale_log2;  // scale * log2(e): scores are exponentiated with exp2
+};
+
+// Enqueue the forward kernel for head dimension D (64 or 128) on `stream`.
+// Returns 0, or -1 if the runtime refused the launch.
+int attn_launch(const AttnParams& p, int D, int causal, hipStream_t stream);

@@ -1,0 +1,85 @@
+// Index maps of the attention-forward kernels, as plain constexpr functions that
+// compile for both host and device.  The kernels use them for every LDS address
+// and every MFMA lane<->element correspondence; the host tests enumerate them to
+// check the operand-pairing ("tag conformity") and no-collision properties that
+// the paper states as data-flow invariants (Section 4, tag assertions at the two
+// MFMA sites of Figure 1), and to count LDS bank conflicts.
+//
+// Tiling (cf. Figure 1: one wavefront owns 32 query rows, K/V stream through LDS
+// in Bc = 64-key tiles):
+//   S^T = K Q^T   per wavefront: A = K tile (32 keys x 16 d), B = Q^T (16 d x 32 queries)
+//   O^T += V^T P^T per wavefront: A = V^T (32 d x 16 keys),   B = P^T (16 keys x 32 queries)
+// so a lane's accumulator column is always one query row: the running max, the
+// running sum and the rescale factor are per-lane scalars.
+#pragma once
+
+#if defined(__HIPCC__)
+#define ATTN_HD __host__ __device__ inline
+#else
+#define ATTN_HD inline
+#endif
+
+namespace attn_layout {
+
+constexpr int kBc = 64;        // keys per LDS tile
+constexpr int kWaveRows = 32;  // query rows per wavefront
+constexpr int kChunk = 16;     // bytes per LDS/global chunk (8 bf16)
+
+// ---- v_mfma_f32_32x32x16_bf16 register layouts (verified on gfx950) -------------
+// A operand: lane l holds A[m = l%32][k = 8*(l/32) + e], e = 0..7
+// B operand: lane l holds B[k = 8*(l/32) + e][n = l%32], e = 0..7
+// C/D      : lane l, register r holds C[m = 8*(r/4) + 4*(l/32) + r%4][n = l%32], r = 0..15
+ATTN_HD constexpr int mfma_ab_k(int lane, int e) { return 8 * (lane / 32) + e; }
+ATTN_HD constexpr int mfma_ab_mn(int lane) { return lane % 32; }
+ATTN_HD constexpr int mfma_c_row(int lane, int r) { return 8 * (r / 4) + 4 * (lane / 32) + r % 4; }
+ATTN_HD constexpr int mfma_c_col(int lane) { return lane % 32; }
+
+// ---- LDS tile layout --------------------------------------------------------------
+// A tile is kBc rows of D bf16 (D*2 bytes), split into D/8 chunks of 16 bytes.
+// Chunk c of row r lives at chunk position (c ^ swizzle(r)) of that row.
+// K is read one 16-byte chunk per lane with 32 consecutive rows per half-wave, so
+// its swizzle must spread 16 consecutive rows over all 64 banks; V is read by the
+// transposing 8-byte load, 4 consecutive rows x 64 contiguous bytes per half-wave,
+// so its swizzle must send 4 consecutive rows to 4 different 64-byte bank groups.
+template <int D> ATTN_HD constexpr int k_swizzle(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+template <int D> ATTN_HD constexpr int v_swizzle(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
+template <int D> ATTN_HD constexpr int tile_bytes() { return kBc * D * 2; }
+template <int D> ATTN_HD constexpr int k_chunk_offset(int row, int chunk) { return row * (D * 2) + ((chunk ^ k_swizzle<D>(row)) * kChunk); }
+template <int D> ATTN_HD constexpr int v_chunk_offset(int row, int chunk) { return row * (D * 2) + ((chunk ^ v_swizzle<D>(row)) * kChunk); }
+
+// ---- S^T = K Q^T operand fetch ------------------------------------------------------
+// MFMA (kb, ks): key block kb (32 keys), reduction step ks (16 d).  Lane l reads the
+// 16-byte chunk holding K[key = 32*kb + l%32][d = 16*ks + 8*(l/32) .. +7] from LDS and
+// pairs it with its register copy of Q[query = l%32][same d].
+ATTN_HD constexpr int qk_key_row(int lane, int kb) { return 32 * kb + lane % 32; }
+ATTN_HD constexpr int qk_chunk(int lane, int ks) { return 2 * ks + lane / 32; }
+ATTN_HD constexpr int qk_d(int lane, int ks, int e) { return 16 * ks + 8 * (lane / 32) + e; }
+
+// ---- P^T as B operand of O^T += V^T P^T ---------------------------------------------
+// The S^T accumulator of key block kb holds, in lane l, keys 32*kb + mfma_c_row(l, r).
+// PV step kk = 2*kb + r/8 consumes registers r = 8*(kk%2) .. +7 as B-operand elements
+// e = r%8, i.e. reduction slot (lane/32, e) of step kk stands for tile key
+//   pv_key(lane, kk, e) = 16*kk + 8*(e/4) + 4*(lane/32) + e%4 .
+ATTN_HD constexpr int pv_key(int lane, int kk, int e) { return 16 * kk + 8 * (e / 4) + 4 * (lane / 32) + e % 4; }
+
+// ---- V^T as A operand: two transposing 8-byte LDS reads per MFMA ---------------------
+// ds_read_b64_tr_b16 (verified on gfx950): lane i of a 16-lane group receives, as its
+// element j, element i%4 of the 8 bytes addressed by lane 4*j + i/4 of its group.
+// For MFMA (dblk, kk), read eg (0/1), lane l therefore ADDRESSES
+//   row   = 16*kk + 8*eg + 4*(l/32) + (l%16)/4
+//   d     = 32*dblk + 16*((l%32)/16) + 4*(l%4)          (4 consecutive d, 8 bytes)
+// and RECEIVES V[key = 16*kk + 8*eg + 4*(l/32) + j][d = 32*dblk + l%32], j = 0..3,
+// which is A-operand element e = 4*eg + j: the same key as pv_key(l, kk, e).
+ATTN_HD constexpr int pv_addr_row(int lane, int kk, int eg) { return 16 * kk + 8 * eg + 4 * (lane / 32) + (lane % 16) / 4; }
+ATTN_HD constexpr int pv_addr_d(int lane, int dblk) { return 32 * dblk + 16 * ((lane % 32) / 16) + 4 * (lane % 4); }
+ATTN_HD constexpr int tr_src_lane(int lane, int j) { return (lane & ~15) + 4 * j + (lane % 16) / 4; }
+ATTN_HD constexpr int tr_src_elem(int lane) { return lane % 4; }
+template <int D> ATTN_HD constexpr int pv_addr_offset(int lane, int dblk, int kk, int eg) {
+    return v_chunk_offset<D>(pv_addr_row(lane, kk, eg), pv_addr_d(lane, dblk) / 8) + 2 * (pv_addr_d(lane, dblk) % 8);
+}
+
+// ---- O^T accumulator -> output element ----------------------------------------------
+// Accumulator dblk, register r of lane l is O[query = l%32][d = 32*dblk + mfma_c_row(l, r)].
+ATTN_HD constexpr int o_d(int lane, int dblk, int r) { return 32 * dblk + mfma_c_row(lane, r); }
+
+}  // namespace attn_layout

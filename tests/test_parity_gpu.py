@@ -1,0 +1,88 @@
+"""Parity of the HIP attention forward (through the C ABI) with the fp64 CPU reference.
+
+Same seeded inputs on both sides, element-by-element comparison at the stated bar:
+max-abs <= 2e-2 and mean-abs <= 2e-3 on O, max-abs <= 1e-3 on LSE.
+"""
+import numpy as np
+import pytest
+
+from paper_2604_18616_amd import inputs as I
+from tests._util import check, oracle_parallel, run_hip
+
+pytestmark = pytest.mark.gpu
+
+
+def small(name, B, Hq, Hkv, Sq, Sk, D, causal, seed, **kw):
+    return I.Workload(name, B, Hq, Hkv, Sq, Sk, D, causal, seed, **kw)
+
+
+SMALL_CASES = [
+    # several 128-row query tiles and 64-key tiles, ragged tails on both axes
+    small("ragged_d128", 2, 4, 2, 200, 333, 128, False, 11),
+    small("ragged_d128_causal", 2, 4, 2, 200, 333, 128, True, 12),
+    small("ragged_d64", 1, 6, 2, 257, 321, 64, False, 13),
+    small("ragged_d64_causal", 1, 6, 2, 257, 321, 64, True, 14),
+    small("square_causal_d128", 1, 8, 2, 512, 512, 128, True, 15),
+    small("square_causal_d64", 2, 2, 2, 384, 384, 64, True, 16),
+    # degenerate sizes
+    small("one_query", 2, 4, 4, 1, 500, 128, False, 17),
+    small("one_query_causal", 2, 4, 1, 1, 500, 64, True, 18),
+    small("one_key", 1, 2, 2, 130, 1, 128, False, 19),
+    small("one_by_one", 1, 1, 1, 1, 1, 64, True, 20),
+    small("more_queries_than_keys_causal", 1, 2, 1, 300, 100, 128, True, 21),   # rows 0..199 see no key
+    small("exact_tiles", 1, 2, 2, 128, 64, 64, False, 22),
+    # shifted keys stress the max subtraction (large common offset in every score of a row)
+    small("shifted_keys", 1, 4, 4, 256, 640, 64, False, 23, sigma=0.5, k_shift=True),
+    small("gqa8", 1, 8, 1, 256, 256, 128, True, 24),
+]
+
+
+def test_config_c1_full():
+    w = I.WORKLOADS["C1"]
+    q, k, v = I.make_qkv(w)
+    o, lse = run_hip(q, k, v, w.causal, w.scale)
+    o_ref, lse_ref = oracle_parallel(q, k, v, w.causal, w.scale)
+    print(w.name, check(o, lse, o_ref, lse_ref, w.name))
+
+
+@pytest.mark.parametrize("w", SMALL_CASES, ids=lambda w: w.name)
+def test_small_shapes_full_oracle(w):
+    q, k, v = I.make_qkv(w)
+    o, lse = run_hip(q, k, v, w.causal, w.scale)
+    o_ref, lse_ref = oracle_parallel(q, k, v, w.causal, w.scale)
+    print(w.name, check(o, lse, o_ref, lse_ref, w.name))
+    if w.causal and w.Sq > w.Sk:
+        assert (lse[:, :, : w.Sq - w.Sk] == -np.inf).all() and (o[:, :, : w.Sq - w.Sk] == 0).all()
+
+
+def test_scale_other_than_rsqrt_d_and_null_lse():
+    w = small("scale", 1, 2, 1, 192, 192, 128, True, 31)
+    q, k, v = I.make_qkv(w)
+    o, lse = run_hip(q, k, v, True, 0.2)
+    o_ref, lse_ref = oracle_parallel(q, k, v, True, 0.2)
+    check(o, lse, o_ref, lse_ref, "scale=0.2")
+    o2, lse2 = run_hip(q, k, v, True, 0.2, want_lse=False)
+    assert np.array_equal(o2, o) and np.isnan(lse2).all()      # lse untouched when NULL is passed
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_full_size_configs_sampled_rows(name):
+    """The benchmark configurations at full size; the reference is evaluated on seeded
+    sample rows per head (always including tile edges and the causal extremes)."""
+    w = I.WORKLOADS[name]
+    q, k, v = I.make_qkv(w)
+    rows = I.sample_rows(w, w.check_rows)
+    o, lse = run_hip(q, k, v, w.causal, w.scale)
+    o_ref, lse_ref = oracle_parallel(q, k, v, w.causal, w.scale, rows=rows)
+    idx = rows.reshape(w.B, w.Hq, -1)
+    o_s = np.take_along_axis(o, idx[..., None], axis=2)
+    lse_s = np.take_along_axis(lse, idx, axis=2)
+    print(name, check(o_s, lse_s, o_ref, lse_ref, name))
+    # properties that hold for every row at any size
+    assert np.isfinite(o).all() and np.isfinite(lse).all()
+    vf = I.bf16_bits_to_f32(v).astype(np.float64)
+    g = w.Hq // w.Hkv
+    if w.causal:                                   # first query row attends to key 0 only
+        assert np.array_equal(o[:, :, 0, :], np.repeat(vf[:, :, 0, :], g, axis=1))
+    vmax = np.repeat(np.abs(vf).max(axis=2), g, axis=1)[:, :, None, :]
+    assert (np.abs(o) <= vmax * (1 + 2 ** -7)).all()   # O is a convex combination of V rows

@@ -32,7 +32,7 @@ extern "C" int attn_fwd(const void* q, const void* k, const void* v, void* o, fl
     p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v;
     p.o = (__bf16*)o; p.lse = lse;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.Sq = Sq; p.Sk = Sk;
-    p.nQt = (int)nQt; p.nblocks = (int)nblocks;
+    p.nQt = 0; p.nblocks = 0;   // set by the launcher
     p.scale = scale;
     p.scale_log2 = (float)((double)scale * 1.4426950408889634074);
     return attn_launch(p, D, causal != 0, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;

@@ -38,6 +38,17 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(unsigned, b);
 }
 
+// Asynchronous 16-byte-per-lane copy HBM -> LDS: lane i's 16 bytes at (base + byte_off)
+// land at LDS address lds_addr + 16*i (verified on gfx950).  Written as inline asm so that
+// the compiler's wait-count pass does not know about the LDS write: given the builtin it
+// puts a full vmcnt(0) wait in front of the next LDS read of ANY buffer, which serialises
+// the prefetch.  Completion is awaited explicitly (s_waitcnt vmcnt) before the barrier
+// that publishes the tile.
+__device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_off, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(byte_off), "s"(base), "s"(lds_addr) : "memory", "m0");
+}
+
 // Exchange between lane l and lane l ^ 32.  v_permlane32_swap(a, b) returns
 //   r0 = { a[0..31], b[0..31] },  r1 = { a[32..63], b[32..63] }     (verified on gfx950),
 // so with b = a, (r0, r1) is (value held by the low-half lane, value held by the
@@ -277,17 +288,280 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
     }
 }
 
+
+// ------------------------------------------------------------------------------------
+// Ping-pong kernel: Sk a multiple of 64.  512 threads = 8 wavefronts x 32 query rows
+// (Br = 256, as in the paper's Figure 1), Bc = 64.
+//
+// * K/V tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no staging
+//   registers) into two buffers each; the swizzle is applied by choosing which global
+//   chunk each lane fetches, since the LDS side of the instruction is lane-contiguous.
+// * Wavefronts w and w+4 share a SIMD.  Group 0 (w < 4) and group 1 (w >= 4) run the same
+//   tile sequence one phase apart, a workgroup barrier between phases: while one group
+//   issues the 32 MFMAs of "PV of tile t-1, then QK^T of tile t", the other runs the
+//   softmax VALU work of its current tile, so the matrix pipe and the vector ALU of every
+//   SIMD are busy at the same time (the paper's "pipelining with wavefront
+//   specialization" stage, Section 8.2, re-derived for two symmetric groups).
+// * The running maximum is only raised when a row's tile maximum exceeds it by more
+//   than 2^kTau (in the exp2 domain); otherwise the stale reference is kept and the
+//   64-register rescale of the O accumulator is skipped.  Any reference gives the same
+//   result after normalisation; probabilities stay below 2^kTau.
+//
+// Phase p (barrier between consecutive phases), for tile t:
+//     group 0:  p = 2t   : issue loads V(t), K(t+1);  PV(t-1);  QK(t)
+//               p = 2t+1 : softmax(t);  wait for own loads
+//     group 1:  p = 2t   : issue loads V(t), K(t+1);  softmax(t-1)
+//               p = 2t+1 : PV(t-1);  QK(t);  wait for own loads
+// K(t) is read in phases 2t, 2t+1 and V(t) in phases 2t+2, 2t+3, so a load issued at the
+// start of phase 2t overwrites a buffer whose last reader finished in phase 2t-1, and has
+// two phases to land.
+// ------------------------------------------------------------------------------------
+constexpr float kTau = 8.0f;
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
+    constexpr int KS = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int TB = tile_bytes<D>();
+    constexpr int kBr = 256;
+    constexpr int CPR = D / 8;                  // 16-byte chunks per row
+    constexpr int ROWS_PER_DMA = 64 / CPR;      // rows covered by one 1 KB wavefront load
+    constexpr int NDMA = TB / 1024 / 8;         // loads per wavefront per tile and matrix
+
+    __shared__ __attribute__((aligned(1024))) char smem[4 * TB];   // K0 K1 V0 V1
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5;
+    const int group = wave >> 2;
+
+    const BlockCoord bc = block_coord<CAUSAL>(blockIdx.x, gridDim.x, p.Hq, p.Hkv, p.nQt);
+    const int q0 = bc.qt * kBr;
+    const int Sq = p.Sq, Sk = p.Sk;
+    const int shift = Sk - Sq;
+
+    const __bf16* qh = p.q + ((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq * D;
+    const __bf16* kh = p.k + ((size_t)bc.b * p.Hkv + bc.hk) * (size_t)Sk * D;
+    const __bf16* vh = p.v + ((size_t)bc.b * p.Hkv + bc.hk) * (size_t)Sk * D;
+
+    // tiles visited by the workgroup / by this wavefront
+    int nT, nTw;
+    const int wrow0 = q0 + wave * kWaveRows;
+    {
+        const int q_last = min(q0 + kBr - 1, Sq - 1);
+        const int lim_max = CAUSAL ? min(Sk - 1, q_last + shift) : Sk - 1;
+        nT = lim_max < 0 ? 0 : lim_max / kBc + 1;
+        const int wlim_max = CAUSAL ? min(Sk - 1, min(wrow0 + kWaveRows - 1, Sq - 1) + shift) : Sk - 1;
+        nTw = (wrow0 >= Sq || wlim_max < 0) ? 0 : wlim_max / kBc + 1;
+    }
+    const int qi = wrow0 + (lane & 31);
+    const int lim = CAUSAL ? min(Sk - 1, qi + shift) : Sk - 1;
+    const int wave_lim_min = CAUSAL ? min(Sk - 1, wrow0 + shift) : Sk - 1;
+
+    // per-lane source byte offsets of this wavefront's direct-to-LDS loads within a tile
+    unsigned kgoff[NDMA], vgoff[NDMA];
+#pragma unroll
+    for (int n = 0; n < NDMA; ++n) {
+        const int row = (wave * NDMA + n) * ROWS_PER_DMA + lane / CPR;
+        const int pos = lane % CPR;
+        kgoff[n] = 2u * (row * D + ((pos ^ k_swizzle<D>(row)) * 8));
+        vgoff[n] = 2u * (row * D + ((pos ^ v_swizzle<D>(row)) * 8));
+    }
+    const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
+    auto issue_k = [&](int t) {
+        const __bf16* src = kh + (size_t)t * kBc * D;
+        const unsigned dst = lds_base + (t & 1) * TB + wave * NDMA * 1024;
+#pragma unroll
+        for (int n = 0; n < NDMA; ++n) dma_to_lds_16B(src, kgoff[n], dst + n * 1024);
+    };
+    auto issue_v = [&](int t) {
+        const __bf16* src = vh + (size_t)t * kBc * D;
+        const unsigned dst = lds_base + (2 + (t & 1)) * TB + wave * NDMA * 1024;
+#pragma unroll
+        for (int n = 0; n < NDMA; ++n) dma_to_lds_16B(src, vgoff[n], dst + n * 1024);
+    };
+    // vmcnt(0) only (expcnt/lgkmcnt fields left at their maxima).  The builtin, unlike
+    // inline asm, also tells the compiler that its own earlier global loads have landed.
+    auto wait_loads = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        asm volatile("" ::: "memory");
+    };
+    auto phase_barrier = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // Q^T B-operand fragments
+    bf16x8 qf[KS];
+    {
+        const __bf16* qrow = qh + (size_t)min(qi, Sq - 1) * D + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qrow + 16 * ks);
+    }
+
+    f32x16 oacc[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+    float m_ref = -INFINITY;   // reference maximum (raw score units) used in the exponent
+    float l_run = 0.f;         // sum over this lane's keys only, relative to m_ref
+    const float c = p.scale_log2;
+
+    f32x16 s[2];
+    unsigned pk[2][8];
+
+    auto qk = [&](int t) {
+        const char* sK = smem + (t & 1) * TB;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const bf16x8 kf = *(const bf16x8*)(sK + k_chunk_offset<D>(qk_key_row(lane, kb), qk_chunk(lane, ks)));
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
+            }
+    };
+    auto pv = [&](int t) {
+        const char* sV = smem + (2 + (t & 1)) * TB;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            u32x4 pw = {pk[kk >> 1][4 * (kk & 1) + 0], pk[kk >> 1][4 * (kk & 1) + 1],
+                        pk[kk >> 1][4 * (kk & 1) + 2], pk[kk >> 1][4 * (kk & 1) + 3]};
+            const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+            for (int dblk = 0; dblk < DB; ++dblk) {
+                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, sV + pv_addr_offset<D>(lane, dblk, kk, 0)));
+                const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, sV + pv_addr_offset<D>(lane, dblk, kk, 1)));
+                typedef __attribute__((ext_vector_type(8))) short s16x8;
+                const s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+                oacc[dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, oacc[dblk], 0, 0, 0);
+            }
+        }
+    };
+    auto softmax = [&](int t) {
+        const int key0 = t * kBc;
+        if (key0 + kBc - 1 > wave_lim_min) {   // causal diagonal
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key0 + 32 * kb + mfma_c_row(lane, r);
+                    if (key > lim) s[kb][r] = -INFINITY;
+                }
+        }
+        float mx = s[0][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
+        mx = max_across_halves(mx);
+        // raise the reference only when some row of this wavefront outgrew it by 2^kTau
+        const bool grow = (mx - m_ref) * c > kTau;           // false for NaN (-inf - -inf)
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+            const float m_new = fmaxf(m_ref, mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = fast_exp2((m_ref - m_use) * c);
+            m_ref = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int i = 0; i < DB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+        }
+        const float mc = (m_ref == -INFINITY ? 0.f : m_ref) * c;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                const float p0 = fast_exp2(fmaf(s[kb][r], c, -mc));
+                const float p1 = fast_exp2(fmaf(s[kb][r + 1], c, -mc));
+                psum += p0 + p1;
+                pk[kb][r >> 1] = pack_bf16x2(p0, p1);
+            }
+        l_run += psum;
+    };
+
+    // ---- prologue: K(0) resident before phase 0
+    if (nT > 0) issue_k(0);
+    wait_loads();
+    phase_barrier();
+
+    if (group == 0) {
+        for (int t = 0; t < nT; ++t) {
+            issue_v(t);
+            if (t + 1 < nT) issue_k(t + 1);
+            if (t > 0 && t - 1 < nTw) pv(t - 1);
+            if (t < nTw) qk(t);
+            phase_barrier();
+            if (t < nTw) softmax(t);
+            wait_loads();
+            phase_barrier();
+        }
+        if (nT > 0 && nT - 1 < nTw) pv(nT - 1);
+        phase_barrier();
+    } else {
+        for (int t = 0; t < nT; ++t) {
+            issue_v(t);
+            if (t + 1 < nT) issue_k(t + 1);
+            if (t > 0 && t - 1 < nTw) softmax(t - 1);
+            phase_barrier();
+            if (t > 0 && t - 1 < nTw) pv(t - 1);
+            if (t < nTw) qk(t);
+            wait_loads();
+            phase_barrier();
+        }
+        if (nT > 0 && nT - 1 < nTw) softmax(nT - 1);
+        phase_barrier();
+        if (nT > 0 && nT - 1 < nTw) pv(nT - 1);
+    }
+
+    // ---- epilogue
+    const float l_tot = sum_across_halves(l_run);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    if (qi < Sq) {
+        __bf16* orow = p.o + (((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq + qi) * D;
+#pragma unroll
+        for (int dblk = 0; dblk < DB; ++dblk)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                u32x2 w;
+                w[0] = pack_bf16x2(oacc[dblk][4 * g4 + 0] * inv, oacc[dblk][4 * g4 + 1] * inv);
+                w[1] = pack_bf16x2(oacc[dblk][4 * g4 + 2] * inv, oacc[dblk][4 * g4 + 3] * inv);
+                *(u32x2*)(orow + o_d(lane, dblk, 4 * g4)) = w;
+            }
+        if (p.lse != nullptr && half == 0) {
+            const float v = l_tot > 0.f ? m_ref * p.scale + logf(l_tot) : -INFINITY;
+            p.lse[((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq + qi] = v;
+        }
+    }
+}
+
 }  // namespace
 
 // Host-side launcher: the only symbol the C-ABI translation unit needs from this file.
-int attn_launch(const AttnParams& p, int D, int causal, hipStream_t stream) {
-    const dim3 grid((unsigned)p.nblocks), block(256);
-    if (D == 128) {
-        if (causal) hipLaunchKernelGGL((attn_fwd_generic<128, true>), grid, block, 0, stream, p);
-        else        hipLaunchKernelGGL((attn_fwd_generic<128, false>), grid, block, 0, stream, p);
+// Key counts that are a multiple of the 64-key tile take the ping-pong kernel (all its
+// loads are in bounds by construction); anything else takes the generic kernel.
+int attn_launch(AttnParams p, int D, int causal, hipStream_t stream) {
+    const bool fast = (p.Sk % 64 == 0);
+    const int br = fast ? 256 : 128;
+    p.nQt = (p.Sq + br - 1) / br;
+    p.nblocks = p.B * p.Hq * p.nQt;
+    const dim3 grid((unsigned)p.nblocks), block(fast ? 512 : 256);
+#define ATTN_LAUNCH(KERNEL, DD, CC) hipLaunchKernelGGL((KERNEL<DD, CC>), grid, block, 0, stream, p)
+    if (fast) {
+        if (D == 128) { if (causal) ATTN_LAUNCH(attn_fwd_pingpong, 128, true); else ATTN_LAUNCH(attn_fwd_pingpong, 128, false); }
+        else          { if (causal) ATTN_LAUNCH(attn_fwd_pingpong, 64, true);  else ATTN_LAUNCH(attn_fwd_pingpong, 64, false); }
     } else {
-        if (causal) hipLaunchKernelGGL((attn_fwd_generic<64, true>), grid, block, 0, stream, p);
-        else        hipLaunchKernelGGL((attn_fwd_generic<64, false>), grid, block, 0, stream, p);
+        if (D == 128) { if (causal) ATTN_LAUNCH(attn_fwd_generic, 128, true); else ATTN_LAUNCH(attn_fwd_generic, 128, false); }
+        else          { if (causal) ATTN_LAUNCH(attn_fwd_generic, 64, true);  else ATTN_LAUNCH(attn_fwd_generic, 64, false); }
     }
+#undef ATTN_LAUNCH
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }

@@ -10,12 +10,12 @@ struct AttnParams {
     __bf16* o;
     float* lse;        // may be null
     int B, Hq, Hkv, Sq, Sk;
-    int nQt;           // query tiles of 128 rows per head
-    int nblocks;       // B * Hq * nQt
+    int nQt;           // query tiles per head (set by the launcher for the kernel it picks)
+    int nblocks;       // B * Hq * nQt  (set by the launcher)
     float scale;       // multiplier on q.k before the softmax
     float scale_log2;  // scale * log2(e): scores are exponentiated with exp2
 };
 
 // Enqueue the forward kernel for head dimension D (64 or 128) on `stream`.
 // Returns 0, or -1 if the runtime refused the launch.
-int attn_launch(const AttnParams& p, int D, int causal, hipStream_t stream);
+int attn_launch(AttnParams p, int D, int causal, hipStream_t stream);

@@ -43,10 +43,11 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
 // the compiler's wait-count pass does not know about the LDS write: given the builtin it
 // puts a full vmcnt(0) wait in front of the next LDS read of ANY buffer, which serialises
 // the prefetch.  Completion is awaited explicitly (s_waitcnt vmcnt) before the barrier
-// that publishes the tile.
+// that publishes the tile.  M0 is written without the compiler knowing; nothing else in
+// these kernels uses M0 (no LDS-DMA builtins, no indirect register indexing, no GWS).
 __device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_off, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(byte_off), "s"(base), "s"(lds_addr) : "memory", "m0");
+                 :: "v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
 }
 
 // Exchange between lane l and lane l ^ 32.  v_permlane32_swap(a, b) returns
@@ -317,6 +318,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
 // two phases to land.
 // ------------------------------------------------------------------------------------
 constexpr float kTau = 8.0f;
+constexpr int kPF = 4;   // MFMA operands kept in flight from LDS (ring of 4-register fragments)
+
+template <int V> struct IntC { static constexpr int value = V; };
+// compile-time loop: f(IntC<I>{}) for I = BEGIN .. END-1, everything inlined
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (BEGIN < END) {
+        f(IntC<BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
+}
 
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
@@ -327,6 +339,8 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     constexpr int CPR = D / 8;                  // 16-byte chunks per row
     constexpr int ROWS_PER_DMA = 64 / CPR;      // rows covered by one 1 KB wavefront load
     constexpr int NDMA = TB / 1024 / 8;         // loads per wavefront per tile and matrix
+    constexpr int NPV = 4 * DB;                 // MFMAs of O^T += V^T P^T per tile
+    constexpr int NQK = 2 * KS;                 // MFMAs of S^T = K Q^T per tile
 
     __shared__ __attribute__((aligned(1024))) char smem[4 * TB];   // K0 K1 V0 V1
 
@@ -369,13 +383,13 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
         vgoff[n] = 2u * (row * D + ((pos ^ v_swizzle<D>(row)) * 8));
     }
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
-    auto issue_k = [&](int t) {
+    auto issue_k = [&](int t) __attribute__((always_inline)) {
         const __bf16* src = kh + (size_t)t * kBc * D;
         const unsigned dst = lds_base + (t & 1) * TB + wave * NDMA * 1024;
 #pragma unroll
         for (int n = 0; n < NDMA; ++n) dma_to_lds_16B(src, kgoff[n], dst + n * 1024);
     };
-    auto issue_v = [&](int t) {
+    auto issue_v = [&](int t) __attribute__((always_inline)) {
         const __bf16* src = vh + (size_t)t * kBc * D;
         const unsigned dst = lds_base + (2 + (t & 1)) * TB + wave * NDMA * 1024;
 #pragma unroll
@@ -383,15 +397,30 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     };
     // vmcnt(0) only (expcnt/lgkmcnt fields left at their maxima).  The builtin, unlike
     // inline asm, also tells the compiler that its own earlier global loads have landed.
-    auto wait_loads = [&]() {
+    auto wait_loads = [&]() __attribute__((always_inline)) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
         asm volatile("" ::: "memory");
     };
-    auto phase_barrier = [&]() {
+    auto phase_barrier = [&]() __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
+
+    // Per-lane LDS read addresses, buffer 0; buffer and row-block select are immediates.
+    //   K operand of MFMA (kb, ks): k_chunk_offset(32*kb + lane%32, 2*ks + half): the swizzle only
+    //   involves lane%16 and the chunk index only bits 4..7 of the address, so step ks is an
+    //   XOR of (ks << 5) into the ks = 0 address.
+    //   V operand of MFMA (dblk, kk), read eg: the swizzle depends on the lane only, the
+    //   rows of (kk, eg) add 256-byte-row multiples: one base per dblk.
+    unsigned kaddr[KS], vaddr[DB];
+    {
+        const unsigned k0 = lds_base + k_chunk_offset<D>(qk_key_row(lane, 0), qk_chunk(lane, 0));
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kaddr[ks] = k0 ^ (unsigned)(ks << 5);
+#pragma unroll
+        for (int dblk = 0; dblk < DB; ++dblk) vaddr[dblk] = lds_base + 2 * TB + pv_addr_offset<D>(lane, dblk, 0, 0);
+    }
 
     // Q^T B-operand fragments
     bf16x8 qf[KS];
@@ -411,40 +440,54 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     const float c = p.scale_log2;
 
     f32x16 s[2];
-    unsigned pk[2][8];
+    bf16x8 pf[4];              // P^T B-operand fragments of the current tile (16 keys each)
 
-    auto qk = [&](int t) {
-        const char* sK = smem + (t & 1) * TB;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 kf = *(const bf16x8*)(sK + k_chunk_offset<D>(qk_key_row(lane, kb), qk_chunk(lane, ks)));
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
-            }
-    };
-    auto pv = [&](int t) {
-        const char* sV = smem + (2 + (t & 1)) * TB;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            u32x4 pw = {pk[kk >> 1][4 * (kk & 1) + 0], pk[kk >> 1][4 * (kk & 1) + 1],
-                        pk[kk >> 1][4 * (kk & 1) + 2], pk[kk >> 1][4 * (kk & 1) + 3]};
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-            for (int dblk = 0; dblk < DB; ++dblk) {
-                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, sV + pv_addr_offset<D>(lane, dblk, kk, 0)));
-                const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, sV + pv_addr_offset<D>(lane, dblk, kk, 1)));
+    // One MFMA phase as a single stream of up to NPV + NQK MFMAs whose LDS operands are
+    // fetched kPF MFMAs ahead: PV of the tile whose V sits in buffer VB, then QK^T of the
+    // tile whose K sits in buffer KB.  sched_barrier pins the issue order step by step so
+    // that the wait counts the compiler derives keep kPF fragments in flight.
+    auto mfma_phase = [&](auto kbuf, auto vbuf, auto do_pv, auto do_qk) __attribute__((always_inline)) {
+        constexpr int KB = decltype(kbuf)::value, VB = decltype(vbuf)::value;
+        constexpr int FIRST = decltype(do_pv)::value ? 0 : NPV;
+        constexpr int LAST = decltype(do_qk)::value ? NPV + NQK : NPV;
+        bf16x8 fr[kPF];
+        auto fetch = [&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            if constexpr (i < NPV) {
+                constexpr int kk = i / DB, dblk = i % DB;
+                constexpr int off = VB * TB + (16 * kk) * (D * 2);
+                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, (size_t)(vaddr[dblk] + off)));
+                const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, (size_t)(vaddr[dblk] + off + 8 * (D * 2))));
                 typedef __attribute__((ext_vector_type(8))) short s16x8;
                 const s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-                oacc[dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, oacc[dblk], 0, 0, 0);
+                fr[i % kPF] = __builtin_bit_cast(bf16x8, vv);
+            } else {
+                constexpr int j = i - NPV, ks = j / 2, kb = j % 2;
+                constexpr int off = KB * TB + (32 * kb) * (D * 2);
+                fr[i % kPF] = *LDS_PTR(const bf16x8, (size_t)(kaddr[ks] + off));
             }
-        }
+        };
+        static_for<FIRST, FIRST + kPF>(fetch);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<FIRST, LAST>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            if constexpr (i < NPV) {
+                constexpr int kk = i / DB, dblk = i % DB;
+                oacc[dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kPF], pf[kk], oacc[dblk], 0, 0, 0);
+            } else {
+                constexpr int j = i - NPV, ks = j / 2, kb = j % 2;
+                if constexpr (ks == 0) {
+                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kPF], qf[ks], zero, 0, 0, 0);
+                } else {
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kPF], qf[ks], s[kb], 0, 0, 0);
+                }
+            }
+            if constexpr (i + kPF < LAST) fetch(IntC<i + kPF>{});
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
-    auto softmax = [&](int t) {
+    auto softmax = [&](int t) __attribute__((always_inline)) {
         const int key0 = t * kBc;
         if (key0 + kBc - 1 > wave_lim_min) {   // causal diagonal
 #pragma unroll
@@ -455,11 +498,15 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
                     if (key > lim) s[kb][r] = -INFINITY;
                 }
         }
-        float mx = s[0][0];
+        // tile maximum of this lane's 32 scores: four independent chains, then the partner lane
+        float mxa[4];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
+        for (int j = 0; j < 4; ++j) mxa[j] = fmaxf(s[0][j], s[1][j]);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
+        for (int r = 4; r < 16; r += 4)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mxa[j] = fmaxf(fmaxf(mxa[j], s[0][r + j]), s[1][r + j]);
+        float mx = fmaxf(fmaxf(mxa[0], mxa[1]), fmaxf(mxa[2], mxa[3]));
         mx = max_across_halves(mx);
         // raise the reference only when some row of this wavefront outgrew it by 2^kTau
         const bool grow = (mx - m_ref) * c > kTau;           // false for NaN (-inf - -inf)
@@ -475,17 +522,22 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
                 for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
         }
         const float mc = (m_ref == -INFINITY ? 0.f : m_ref) * c;
-        float psum = 0.f;
+        float ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb) {
+            unsigned pk[8];
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
                 const float p0 = fast_exp2(fmaf(s[kb][r], c, -mc));
                 const float p1 = fast_exp2(fmaf(s[kb][r + 1], c, -mc));
-                psum += p0 + p1;
-                pk[kb][r >> 1] = pack_bf16x2(p0, p1);
+                ps[(r >> 1) & 3] += p0 + p1;
+                pk[r >> 1] = pack_bf16x2(p0, p1);
             }
-        l_run += psum;
+            const u32x4 lo = {pk[0], pk[1], pk[2], pk[3]}, hi = {pk[4], pk[5], pk[6], pk[7]};
+            pf[2 * kb] = __builtin_bit_cast(bf16x8, lo);
+            pf[2 * kb + 1] = __builtin_bit_cast(bf16x8, hi);
+        }
+        l_run += (ps[0] + ps[1]) + (ps[2] + ps[3]);
     };
 
     // ---- prologue: K(0) resident before phase 0
@@ -493,33 +545,87 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     wait_loads();
     phase_barrier();
 
-    if (group == 0) {
-        for (int t = 0; t < nT; ++t) {
-            issue_v(t);
-            if (t + 1 < nT) issue_k(t + 1);
-            if (t > 0 && t - 1 < nTw) pv(t - 1);
-            if (t < nTw) qk(t);
+    // The tile loop is split by regime so that the steady state (every wavefront has both
+    // PV(t-1) and QK(t)) is branch-free straight-line code, unrolled by two for the buffer
+    // parity: t = 0 (QK only), 1 <= t < nTw (both), t = nTw (PV only), t > nTw (this
+    // wavefront is past its causal limit and only keeps the barriers and its share of the
+    // loads).  Every path executes 2 barriers per tile plus one at the end.
+    auto loads = [&](int t) __attribute__((always_inline)) {
+        issue_v(t);
+        if (t + 1 < nT) issue_k(t + 1);
+    };
+    auto pv_only = [&](int t) __attribute__((always_inline)) {     // PV(t), V(t) in buffer t & 1
+        if (t & 1) mfma_phase(IntC<0>{}, IntC<1>{}, IntC<1>{}, IntC<0>{});
+        else       mfma_phase(IntC<0>{}, IntC<0>{}, IntC<1>{}, IntC<0>{});
+    };
+    auto idle_tiles = [&](int t) __attribute__((always_inline)) {
+        for (; t < nT; ++t) { loads(t); phase_barrier(); wait_loads(); phase_barrier(); }
+    };
+    if (nTw == 0) {
+        idle_tiles(0);
+        phase_barrier();
+    } else if (group == 0) {
+        loads(0);
+        mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, IntC<1>{});
+        phase_barrier();
+        softmax(0);
+        wait_loads();
+        phase_barrier();
+        int t = 1;
+        auto step = [&](auto par, int tt) __attribute__((always_inline)) {
+            constexpr int PAR = decltype(par)::value;
+            loads(tt);
+            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, IntC<1>{});
             phase_barrier();
-            if (t < nTw) softmax(t);
+            softmax(tt);
             wait_loads();
             phase_barrier();
+        };
+        for (; t + 1 < nTw; t += 2) { step(IntC<1>{}, t); step(IntC<0>{}, t + 1); }
+        if (t < nTw) { step(IntC<1>{}, t); ++t; }
+        if (t < nT) {
+            loads(t);
+            pv_only(t - 1);
+            phase_barrier();
+            wait_loads();
+            phase_barrier();
+            idle_tiles(t + 1);
+        } else {
+            pv_only(nT - 1);
         }
-        if (nT > 0 && nT - 1 < nTw) pv(nT - 1);
         phase_barrier();
     } else {
-        for (int t = 0; t < nT; ++t) {
-            issue_v(t);
-            if (t + 1 < nT) issue_k(t + 1);
-            if (t > 0 && t - 1 < nTw) softmax(t - 1);
+        loads(0);
+        phase_barrier();
+        mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, IntC<1>{});
+        wait_loads();
+        phase_barrier();
+        int t = 1;
+        auto step = [&](auto par, int tt) __attribute__((always_inline)) {
+            constexpr int PAR = decltype(par)::value;
+            loads(tt);
+            softmax(tt - 1);
             phase_barrier();
-            if (t > 0 && t - 1 < nTw) pv(t - 1);
-            if (t < nTw) qk(t);
+            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, IntC<1>{});
             wait_loads();
             phase_barrier();
+        };
+        for (; t + 1 < nTw; t += 2) { step(IntC<1>{}, t); step(IntC<0>{}, t + 1); }
+        if (t < nTw) { step(IntC<1>{}, t); ++t; }
+        if (t < nT) {
+            loads(t);
+            softmax(t - 1);
+            phase_barrier();
+            pv_only(t - 1);
+            wait_loads();
+            phase_barrier();
+            idle_tiles(t + 1);
+            phase_barrier();
+        } else {
+            softmax(nT - 1);
+            phase_barrier();
+            pv_only(nT - 1);
         }
-        if (nT > 0 && nT - 1 < nTw) softmax(nT - 1);
-        phase_barrier();
-        if (nT > 0 && nT - 1 < nTw) pv(nT - 1);
     }
 
     // ---- epilogue

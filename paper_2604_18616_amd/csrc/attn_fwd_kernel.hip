@@ -308,14 +308,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
 //   64-register rescale of the O accumulator is skipped.  Any reference gives the same
 //   result after normalisation; probabilities stay below 2^kTau.
 //
-// Phase p (barrier between consecutive phases), for tile t:
-//     group 0:  p = 2t   : issue loads V(t), K(t+1);  PV(t-1);  QK(t)
-//               p = 2t+1 : softmax(t);  wait for own loads
-//     group 1:  p = 2t   : issue loads V(t), K(t+1);  softmax(t-1)
-//               p = 2t+1 : PV(t-1);  QK(t);  wait for own loads
-// K(t) is read in phases 2t, 2t+1 and V(t) in phases 2t+2, 2t+3, so a load issued at the
-// start of phase 2t overwrites a buffer whose last reader finished in phase 2t-1, and has
-// two phases to land.
+// Tile period T (one workgroup barrier per period):
+//     group 0:  PV(T-1), QK(T) as one MFMA stream, its share of the loads interleaved;  softmax(T)
+//     group 1:  softmax(T-1), its share of the loads interleaved;  PV(T-1), QK(T)
+// Both groups read K(T) and V(T-1) in period T; the loads of K(T+1) and V(T) issued in period
+// T overwrite buffers last read in period T-1, are awaited by the issuing wavefront at the
+// end of period T and published by the barrier that closes it.
 // ------------------------------------------------------------------------------------
 constexpr float kTau = 8.0f;
 constexpr int kPF = 4;   // MFMA operands kept in flight from LDS (ring of 4-register fragments)
@@ -373,27 +371,37 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     const int lim = CAUSAL ? min(Sk - 1, qi + shift) : Sk - 1;
     const int wave_lim_min = CAUSAL ? min(Sk - 1, wrow0 + shift) : Sk - 1;
 
-    // per-lane source byte offsets of this wavefront's direct-to-LDS loads within a tile
-    unsigned kgoff[NDMA], vgoff[NDMA];
-#pragma unroll
-    for (int n = 0; n < NDMA; ++n) {
-        const int row = (wave * NDMA + n) * ROWS_PER_DMA + lane / CPR;
+    // Per-lane source byte offset of this wavefront's direct-to-LDS loads within a tile.
+    // Load n of a wavefront is 1 KB instruction number wave + 8*n of the tile: its rows lie
+    // 8*ROWS_PER_DMA (a multiple of 16) below those of load 0, so the swizzle is the same and
+    // the n-dependence is a constant that folds into the scalar base / LDS destination.
+    unsigned kgoff, vgoff;
+    {
+        const int row = wave * ROWS_PER_DMA + lane / CPR;
         const int pos = lane % CPR;
-        kgoff[n] = 2u * (row * D + ((pos ^ k_swizzle<D>(row)) * 8));
-        vgoff[n] = 2u * (row * D + ((pos ^ v_swizzle<D>(row)) * 8));
+        kgoff = 2u * (row * D + ((pos ^ k_swizzle<D>(row)) * 8));
+        vgoff = 2u * (row * D + ((pos ^ v_swizzle<D>(row)) * 8));
     }
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
+    // The loads of one phase pair, one instruction at a time: slot j < NDMA is part j of V(t),
+    // slot j >= NDMA part j - NDMA of K(t+1).  Issued spread over the phase: a burst from all
+    // eight wavefronts right after the barrier queues 32 KB of requests in front of the
+    // address unit and stalls the issuing wavefronts.
+    auto dma_part = [&](const __bf16* head, unsigned lane_off, int t, int buf, int n) __attribute__((always_inline)) {
+        const __bf16* src = head + ((size_t)t * kBc + n * 8 * ROWS_PER_DMA) * D;
+        dma_to_lds_16B(src, lane_off, lds_base + buf * TB + (wave + 8 * n) * 1024);
+    };
     auto issue_k = [&](int t) __attribute__((always_inline)) {
-        const __bf16* src = kh + (size_t)t * kBc * D;
-        const unsigned dst = lds_base + (t & 1) * TB + wave * NDMA * 1024;
 #pragma unroll
-        for (int n = 0; n < NDMA; ++n) dma_to_lds_16B(src, kgoff[n], dst + n * 1024);
+        for (int n = 0; n < NDMA; ++n) dma_part(kh, kgoff, t, t & 1, n);
     };
     auto issue_v = [&](int t) __attribute__((always_inline)) {
-        const __bf16* src = vh + (size_t)t * kBc * D;
-        const unsigned dst = lds_base + (2 + (t & 1)) * TB + wave * NDMA * 1024;
 #pragma unroll
-        for (int n = 0; n < NDMA; ++n) dma_to_lds_16B(src, vgoff[n], dst + n * 1024);
+        for (int n = 0; n < NDMA; ++n) dma_part(vh, vgoff, t, 2 + (t & 1), n);
+    };
+    auto dma_slot = [&](int t, int j) __attribute__((always_inline)) {
+        if (j < NDMA) dma_part(vh, vgoff, t, 2 + (t & 1), j);
+        else if (t + 1 < nT) dma_part(kh, kgoff, t + 1, (t + 1) & 1, j - NDMA);
     };
     // vmcnt(0) only (expcnt/lgkmcnt fields left at their maxima).  The builtin, unlike
     // inline asm, also tells the compiler that its own earlier global loads have landed.
@@ -413,11 +421,9 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     //   XOR of (ks << 5) into the ks = 0 address.
     //   V operand of MFMA (dblk, kk), read eg: the swizzle depends on the lane only, the
     //   rows of (kk, eg) add 256-byte-row multiples: one base per dblk.
-    unsigned kaddr[KS], vaddr[DB];
+    unsigned kaddr0, vaddr[DB];
     {
-        const unsigned k0 = lds_base + k_chunk_offset<D>(qk_key_row(lane, 0), qk_chunk(lane, 0));
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kaddr[ks] = k0 ^ (unsigned)(ks << 5);
+        kaddr0 = lds_base + k_chunk_offset<D>(qk_key_row(lane, 0), qk_chunk(lane, 0));
 #pragma unroll
         for (int dblk = 0; dblk < DB; ++dblk) vaddr[dblk] = lds_base + 2 * TB + pv_addr_offset<D>(lane, dblk, 0, 0);
     }
@@ -442,32 +448,43 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     f32x16 s[2];
     bf16x8 pf[4];              // P^T B-operand fragments of the current tile (16 keys each)
 
-    // One MFMA phase as a single stream of up to NPV + NQK MFMAs whose LDS operands are
-    // fetched kPF MFMAs ahead: PV of the tile whose V sits in buffer VB, then QK^T of the
-    // tile whose K sits in buffer KB.  sched_barrier pins the issue order step by step so
-    // that the wait counts the compiler derives keep kPF fragments in flight.
-    auto mfma_phase = [&](auto kbuf, auto vbuf, auto do_pv, auto do_qk) __attribute__((always_inline)) {
+    // One MFMA phase is a single stream of up to NPV + NQK MFMAs whose LDS operands are
+    // fetched kPF MFMAs ahead into the ring fr: PV of the tile whose V sits in buffer VB, then
+    // QK^T of the tile whose K sits in buffer KB.  The first kPF fetches are issued by
+    // prefetch_* BEFORE the barrier that opens the phase (their tiles are already published),
+    // so the LDS latency of the phase start is hidden behind the barrier.  sched_barrier pins
+    // the issue order step by step so that the wait counts the compiler derives keep kPF
+    // fragments in flight.
+    bf16x8 fr[kPF];
+    auto fetch_op = [&](auto kbuf, auto vbuf, auto ic) __attribute__((always_inline)) {
         constexpr int KB = decltype(kbuf)::value, VB = decltype(vbuf)::value;
+        constexpr int i = decltype(ic)::value;
+        if constexpr (i < NPV) {
+            constexpr int kk = i / DB, dblk = i % DB;
+            constexpr int off = VB * TB + (16 * kk) * (D * 2);
+            const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, (size_t)(vaddr[dblk] + off)));
+            const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, (size_t)(vaddr[dblk] + off + 8 * (D * 2))));
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+            const s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+            fr[i % kPF] = __builtin_bit_cast(bf16x8, vv);
+        } else {
+            constexpr int j = i - NPV, ks = j / 2, kb = j % 2;
+            constexpr int off = KB * TB + (32 * kb) * (D * 2);
+            fr[i % kPF] = *LDS_PTR(const bf16x8, (size_t)((kaddr0 ^ (unsigned)(ks << 5)) + off));
+        }
+    };
+    auto prefetch_pv = [&](auto vbuf) __attribute__((always_inline)) {
+        static_for<0, kPF>([&](auto ic) __attribute__((always_inline)) { fetch_op(IntC<0>{}, vbuf, ic); });
+    };
+    auto prefetch_pv_dyn = [&](int t) __attribute__((always_inline)) {    // V(t) sits in buffer t & 1
+        if (t & 1) prefetch_pv(IntC<1>{}); else prefetch_pv(IntC<0>{});
+    };
+    auto prefetch_qk = [&](auto kbuf) __attribute__((always_inline)) {
+        static_for<NPV, NPV + kPF>([&](auto ic) __attribute__((always_inline)) { fetch_op(kbuf, IntC<0>{}, ic); });
+    };
+    auto mfma_run = [&](auto kbuf, auto vbuf, auto do_pv, auto do_qk, int dma_t) __attribute__((always_inline)) {
         constexpr int FIRST = decltype(do_pv)::value ? 0 : NPV;
         constexpr int LAST = decltype(do_qk)::value ? NPV + NQK : NPV;
-        bf16x8 fr[kPF];
-        auto fetch = [&](auto ic) __attribute__((always_inline)) {
-            constexpr int i = decltype(ic)::value;
-            if constexpr (i < NPV) {
-                constexpr int kk = i / DB, dblk = i % DB;
-                constexpr int off = VB * TB + (16 * kk) * (D * 2);
-                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, (size_t)(vaddr[dblk] + off)));
-                const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, (size_t)(vaddr[dblk] + off + 8 * (D * 2))));
-                typedef __attribute__((ext_vector_type(8))) short s16x8;
-                const s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-                fr[i % kPF] = __builtin_bit_cast(bf16x8, vv);
-            } else {
-                constexpr int j = i - NPV, ks = j / 2, kb = j % 2;
-                constexpr int off = KB * TB + (32 * kb) * (D * 2);
-                fr[i % kPF] = *LDS_PTR(const bf16x8, (size_t)(kaddr[ks] + off));
-            }
-        };
-        static_for<FIRST, FIRST + kPF>(fetch);
         __builtin_amdgcn_sched_barrier(0);
         static_for<FIRST, LAST>([&](auto ic) __attribute__((always_inline)) {
             constexpr int i = decltype(ic)::value;
@@ -483,11 +500,18 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
                     s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kPF], qf[ks], s[kb], 0, 0, 0);
                 }
             }
-            if constexpr (i + kPF < LAST) fetch(IntC<i + kPF>{});
+            if constexpr (i + kPF < LAST) fetch_op(kbuf, vbuf, IntC<i + kPF>{});
+            // loads of this phase pair, early in the stream: they must land before the phase ends
+            constexpr int NSLOT = 2 * NDMA;
+            if constexpr ((i - FIRST) % 2 == 1 && (i - FIRST) / 2 < NSLOT) {
+                if (dma_t >= 0) dma_slot(dma_t, (i - FIRST) / 2);
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
     };
-    auto softmax = [&](int t) __attribute__((always_inline)) {
+
+    auto softmax = [&](int t, int dma_t) __attribute__((always_inline)) {
+        __builtin_amdgcn_s_setprio(2);
         const int key0 = t * kBc;
         if (key0 + kBc - 1 > wave_lim_min) {   // causal diagonal
 #pragma unroll
@@ -507,6 +531,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) mxa[j] = fmaxf(fmaxf(mxa[j], s[0][r + j]), s[1][r + j]);
         float mx = fmaxf(fmaxf(mxa[0], mxa[1]), fmaxf(mxa[2], mxa[3]));
+        if (dma_t >= 0) dma_slot(dma_t, 0);
         mx = max_across_halves(mx);
         // raise the reference only when some row of this wavefront outgrew it by 2^kTau
         const bool grow = (mx - m_ref) * c > kTau;           // false for NaN (-inf - -inf)
@@ -525,6 +550,10 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
         float ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
+            if (dma_t >= 0) {
+                if (NDMA == 2) { dma_slot(dma_t, 1 + kb); if (kb == 1) dma_slot(dma_t, 3); }
+                else if (kb == 1) dma_slot(dma_t, 1);
+            }
             unsigned pk[8];
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
@@ -538,6 +567,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
             pf[2 * kb + 1] = __builtin_bit_cast(bf16x8, hi);
         }
         l_run += (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        __builtin_amdgcn_s_setprio(0);
     };
 
     // ---- prologue: K(0) resident before phase 0
@@ -554,77 +584,73 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
         issue_v(t);
         if (t + 1 < nT) issue_k(t + 1);
     };
-    auto pv_only = [&](int t) __attribute__((always_inline)) {     // PV(t), V(t) in buffer t & 1
-        if (t & 1) mfma_phase(IntC<0>{}, IntC<1>{}, IntC<1>{}, IntC<0>{});
-        else       mfma_phase(IntC<0>{}, IntC<0>{}, IntC<1>{}, IntC<0>{});
+    auto mfma_phase = [&](auto kbuf, auto vbuf, auto do_pv, auto do_qk, int dma_t) __attribute__((always_inline)) {
+        if constexpr (decltype(do_pv)::value) prefetch_pv(vbuf); else prefetch_qk(kbuf);
+        mfma_run(kbuf, vbuf, do_pv, do_qk, dma_t);
     };
+    auto pv_only = [&](int t, int dma_t) __attribute__((always_inline)) {   // PV(t), V(t) in buffer t & 1
+        if (t & 1) mfma_phase(IntC<0>{}, IntC<1>{}, IntC<1>{}, IntC<0>{}, dma_t);
+        else       mfma_phase(IntC<0>{}, IntC<0>{}, IntC<1>{}, IntC<0>{}, dma_t);
+    };
+    // One barrier per tile period T.  In period T both groups read K(T) and V(T-1); the loads
+    // of K(T+1) and V(T) are issued early in the period (their buffers were last read in
+    // period T-1), awaited by the issuing wavefront at its end and published by the barrier.
+    //     group 0:  PV(T-1), QK(T) [MFMA stream]  then  softmax(T)
+    //     group 1:  softmax(T-1)                  then  PV(T-1), QK(T) [MFMA stream]
+    // so the two wavefronts of a SIMD start every period in opposite kinds of work and
+    // trade places without a barrier in between.
     auto idle_tiles = [&](int t) __attribute__((always_inline)) {
-        for (; t < nT; ++t) { loads(t); phase_barrier(); wait_loads(); phase_barrier(); }
+        for (; t < nT; ++t) { loads(t); wait_loads(); phase_barrier(); }
     };
     if (nTw == 0) {
         idle_tiles(0);
-        phase_barrier();
     } else if (group == 0) {
-        loads(0);
-        mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, IntC<1>{});
-        phase_barrier();
-        softmax(0);
+        mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, IntC<1>{}, 0);
+        softmax(0, -1);
         wait_loads();
         phase_barrier();
         int t = 1;
         auto step = [&](auto par, int tt) __attribute__((always_inline)) {
             constexpr int PAR = decltype(par)::value;
-            loads(tt);
-            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, IntC<1>{});
-            phase_barrier();
-            softmax(tt);
+            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, IntC<1>{}, tt);
+            softmax(tt, -1);
             wait_loads();
             phase_barrier();
         };
         for (; t + 1 < nTw; t += 2) { step(IntC<1>{}, t); step(IntC<0>{}, t + 1); }
         if (t < nTw) { step(IntC<1>{}, t); ++t; }
         if (t < nT) {
-            loads(t);
-            pv_only(t - 1);
-            phase_barrier();
+            pv_only(t - 1, t);
             wait_loads();
             phase_barrier();
             idle_tiles(t + 1);
         } else {
-            pv_only(nT - 1);
+            pv_only(nT - 1, -1);
         }
-        phase_barrier();
     } else {
         loads(0);
-        phase_barrier();
-        mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, IntC<1>{});
+        mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, IntC<1>{}, -1);
         wait_loads();
         phase_barrier();
         int t = 1;
         auto step = [&](auto par, int tt) __attribute__((always_inline)) {
             constexpr int PAR = decltype(par)::value;
-            loads(tt);
-            softmax(tt - 1);
-            phase_barrier();
-            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, IntC<1>{});
+            softmax(tt - 1, tt);
+            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, IntC<1>{}, -1);
             wait_loads();
             phase_barrier();
         };
         for (; t + 1 < nTw; t += 2) { step(IntC<1>{}, t); step(IntC<0>{}, t + 1); }
         if (t < nTw) { step(IntC<1>{}, t); ++t; }
         if (t < nT) {
-            loads(t);
-            softmax(t - 1);
-            phase_barrier();
-            pv_only(t - 1);
+            softmax(t - 1, t);
+            pv_only(t - 1, -1);
             wait_loads();
             phase_barrier();
             idle_tiles(t + 1);
-            phase_barrier();
         } else {
-            softmax(nT - 1);
-            phase_barrier();
-            pv_only(nT - 1);
+            softmax(nT - 1, -1);
+            pv_only(nT - 1, -1);
         }
     }
 

@@ -101,6 +101,14 @@ WORKLOADS = {
 }
 
 
+# Further shapes: the paper's own attention workload (Section 8: causal GQA, batch 16, 8 query
+# heads on 1 kv head, d = 128, sequence 1024 .. 16384) and a long non-causal case that
+# isolates the steady state of the kernels (no diagonal, no ragged last wave of workgroups).
+for _s in (1024, 2048, 4096, 8192, 16384):
+    WORKLOADS["P%d" % _s] = Workload("P%d" % _s, 16, 8, 1, _s, _s, 128, True, 2000 + _s, check_rows=64)
+WORKLOADS["N8K"] = Workload("N8K", 1, 32, 8, 8192, 8192, 128, False, 3001, check_rows=64)
+
+
 def make_qkv(w: Workload):
     """Q [B,Hq,Sq,D], K, V [B,Hkv,Sk,D] as uint16 arrays of bf16 bit patterns."""
     nq = w.B * w.Hq * w.Sq * w.D

@@ -50,6 +50,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU reference leg (profiling runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain device copy of known size instead (scales the rocprofv3 FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (attention shards over batch and kv heads with "
@@ -65,6 +67,18 @@ def main() -> int:
     lib = binding.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.copy_calibration:
+        # 256 MiB read + 256 MiB written per copy kernel: the known traffic the HBM counters are scaled by
+        n = 256 << 20
+        src = torch.arange(n // 4, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": n, "bytes_written_per_copy": n,
+                          "copies": args.steps}))
+        return 0
 
     w = I.WORKLOADS[args.workload]
     qb, kb, vb = I.make_qkv(w)

@@ -335,8 +335,8 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     constexpr int TB = tile_bytes<D>();
     constexpr int kBr = 256;
     constexpr int CPR = D / 8;                  // 16-byte chunks per row
-    constexpr int ROWS_PER_DMA = 64 / CPR;      // rows covered by one 1 KB wavefront load
-    constexpr int NDMA = TB / 1024 / 8;         // loads per wavefront per tile and matrix
+    constexpr int ROWS_PER_DMA = dma_rows_per_inst<D>();   // rows covered by one 1 KB wavefront load
+    constexpr int NDMA = dma_insts_per_wave<D>();          // loads per wavefront per tile and matrix
     constexpr int NPV = 4 * DB;                 // MFMAs of O^T += V^T P^T per tile
     constexpr int NQK = 2 * KS;                 // MFMAs of S^T = K Q^T per tile
 
@@ -371,17 +371,10 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     const int lim = CAUSAL ? min(Sk - 1, qi + shift) : Sk - 1;
     const int wave_lim_min = CAUSAL ? min(Sk - 1, wrow0 + shift) : Sk - 1;
 
-    // Per-lane source byte offset of this wavefront's direct-to-LDS loads within a tile.
-    // Load n of a wavefront is 1 KB instruction number wave + 8*n of the tile: its rows lie
-    // 8*ROWS_PER_DMA (a multiple of 16) below those of load 0, so the swizzle is the same and
-    // the n-dependence is a constant that folds into the scalar base / LDS destination.
-    unsigned kgoff, vgoff;
-    {
-        const int row = wave * ROWS_PER_DMA + lane / CPR;
-        const int pos = lane % CPR;
-        kgoff = 2u * (row * D + ((pos ^ k_swizzle<D>(row)) * 8));
-        vgoff = 2u * (row * D + ((pos ^ v_swizzle<D>(row)) * 8));
-    }
+    // Per-lane source byte offset of this wavefront's direct-to-LDS loads within a tile
+    // (load n = 0; load n adds the constant 8 * ROWS_PER_DMA rows, folded into the base).
+    const unsigned kgoff = 2u * dma_src_elem<D, false>(wave, 0, lane);
+    const unsigned vgoff = 2u * dma_src_elem<D, true>(wave, 0, lane);
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
     // The loads of one phase pair, one instruction at a time: slot j < NDMA is part j of V(t),
     // slot j >= NDMA part j - NDMA of K(t+1).  Issued spread over the phase: a burst from all
@@ -389,7 +382,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     // address unit and stalls the issuing wavefronts.
     auto dma_part = [&](const __bf16* head, unsigned lane_off, int t, int buf, int n) __attribute__((always_inline)) {
         const __bf16* src = head + ((size_t)t * kBc + n * 8 * ROWS_PER_DMA) * D;
-        dma_to_lds_16B(src, lane_off, lds_base + buf * TB + (wave + 8 * n) * 1024);
+        dma_to_lds_16B(src, lane_off, lds_base + buf * TB + dma_dst_offset<D>(wave, n, 0));
     };
     auto issue_k = [&](int t) __attribute__((always_inline)) {
 #pragma unroll

@@ -1,0 +1,81 @@
+"""The C-ABI library: it loads, exports every symbol include/attn.h declares, and every
+argument error is reported before any HIP call (so these run on a machine with no GPU)."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+from paper_2604_18616_amd import binding
+from paper_2604_18616_amd.inputs import WORKLOADS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "attn.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load_library()       # builds only if no built library is present
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", src)
+
+
+def test_header_declares_the_boundary():
+    names = declared_functions()
+    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops"}
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+    assert lib.attn_version() >= 100
+
+
+def test_error_codes_match_header(lib):
+    src = open(HEADER).read()
+    codes = {m.group(1): int(m.group(2)) for m in re.finditer(r"(ATTN_[A-Z_]+)\s*=\s*(-?\d+)", src)}
+    assert codes["ATTN_OK"] == 0 and len(codes) == 7
+    msgs = {c: lib.attn_strerror(c).decode() for c in codes.values()}
+    assert len(set(msgs.values())) == len(msgs)            # distinct, non-empty messages
+    assert all(msgs.values())
+    assert "unknown" in lib.attn_strerror(-99).decode()
+
+
+A16 = 0x1000   # fake, aligned, never dereferenced: validation returns before any HIP call
+
+
+def call(lib, q=A16, k=A16, v=A16, o=A16, lse=A16, B=1, Hq=4, Hkv=2, Sq=128, Sk=128, D=128, causal=1, scale=0.1):
+    return lib.attn_fwd(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, causal, scale, None)
+
+
+def test_argument_errors_are_reported_without_a_gpu(lib):
+    assert call(lib, q=None) == -1 and call(lib, k=None) == -1 and call(lib, v=None) == -1 and call(lib, o=None) == -1
+    for kw in (dict(B=0), dict(Hq=0), dict(Hkv=0), dict(Sq=0), dict(Sk=-3), dict(D=0), dict(Hq=5, Hkv=2)):
+        assert call(lib, **kw) == -2, kw
+    assert call(lib, B=1 << 20, Hq=1 << 10, Hkv=1, Sq=1 << 20) == -2           # grid overflow
+    for D in (32, 96, 256, 80):
+        assert call(lib, D=D) == -3
+    for kw in (dict(q=A16 + 2), dict(k=A16 + 8), dict(v=A16 + 4), dict(o=A16 + 1), dict(lse=A16 + 2)):
+        assert call(lib, **kw) == -4, kw
+    for s in (0.0, -0.5, math.nan, math.inf, -math.inf):
+        assert call(lib, scale=s) == -5, s
+
+
+def test_flops_helper_matches_workload_table(lib):
+    for w in WORKLOADS.values():
+        assert lib.attn_fwd_flops(w.B, w.Hq, w.Hkv, w.Sq, w.Sk, w.D, int(w.causal)) == w.flops()
+    assert lib.attn_fwd_flops(1, 1, 1, 3, 5, 64, 1) == 4 * 64 * (3 + 4 + 5)     # bottom-right aligned
+    assert lib.attn_fwd_flops(1, 1, 1, 5, 3, 64, 1) == 4 * 64 * (0 + 0 + 1 + 2 + 3)
+    assert lib.attn_fwd_flops(1, 3, 2, 4, 4, 64, 0) == -1.0
+
+
+def test_python_binding_refuses_cpu_tensors():
+    torch = pytest.importorskip("torch")
+    q = torch.zeros(1, 2, 8, 64, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        binding.attn_fwd(q, q, q)

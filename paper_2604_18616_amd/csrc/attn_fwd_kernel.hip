@@ -303,10 +303,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
 //   softmax VALU work of its current tile, so the matrix pipe and the vector ALU of every
 //   SIMD are busy at the same time (the paper's "pipelining with wavefront
 //   specialization" stage, Section 8.2, re-derived for two symmetric groups).
-// * The running maximum is only raised when a row's tile maximum exceeds it by more
-//   than 2^kTau (in the exp2 domain); otherwise the stale reference is kept and the
-//   64-register rescale of the O accumulator is skipped.  Any reference gives the same
-//   result after normalisation; probabilities stay below 2^kTau.
+// * No running maximum on the common path: scores are exponentiated against a stale
+//   reference m_ref (set from the true maximum on the wavefront's first tile).  Any
+//   reference gives the same result after normalisation, and bf16 P keeps its relative
+//   precision at any magnitude; only when a partial row sum reaches 2^64 (or is not finite)
+//   is the tile redone with the true maximum and l and O are rescaled.  This drops the max
+//   reduction, the lane exchange and the 64-register rescale from almost every tile.
 //
 // Tile period T (one workgroup barrier per period):
 //     group 0:  PV(T-1), QK(T) as one MFMA stream, its share of the loads interleaved;  softmax(T)
@@ -315,8 +317,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
 // T overwrite buffers last read in period T-1, are awaited by the issuing wavefront at the
 // end of period T and published by the barrier that closes it.
 // ------------------------------------------------------------------------------------
-constexpr float kTau = 8.0f;
-constexpr int kPF = 4;   // MFMA operands kept in flight from LDS (ring of 4-register fragments)
+constexpr float kBig = 18446744073709551616.0f;   // 2^64: bound on a partial row sum of the fast path
+constexpr int kPF = 3;   // MFMA operands kept in flight from LDS (ring of 4-register fragments)
 
 template <int V> struct IntC { static constexpr int value = V; };
 // compile-time loop: f(IntC<I>{}) for I = BEGIN .. END-1, everything inlined
@@ -507,59 +509,67 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
         __builtin_amdgcn_s_setprio(2);
         const int key0 = t * kBc;
         if (key0 + kBc - 1 > wave_lim_min) {   // causal diagonal
+            // key(kb, r) = key0 + 32*kb + 8*(r/4) + 4*half + r%4 is masked iff it exceeds lim:
+            // compare the per-lane room (lim - key0 - 4*half) with compile-time constants
+            const int room = lim - key0 - 4 * half;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = key0 + 32 * kb + mfma_c_row(lane, r);
-                    if (key > lim) s[kb][r] = -INFINITY;
-                }
+                for (int r = 0; r < 16; ++r)
+                    if (32 * kb + 8 * (r / 4) + r % 4 > room) s[kb][r] = -INFINITY;
         }
-        // tile maximum of this lane's 32 scores: four independent chains, then the partner lane
-        float mxa[4];
+        // Exponentiate against the current reference m_ref without looking for the tile maximum:
+        // bf16 and fp32 share the exponent range, so P keeps its relative precision whatever the
+        // reference is, as long as nothing overflows.  Only if a partial row sum leaves
+        // [0, kBig) (a score outgrew the reference by more than log2(kBig) in the exp2 domain,
+        // or this is the first tile of the wavefront) is the tile redone on the slow path below,
+        // which finds the true maximum, moves the reference and rescales l and O.
+        auto exponentiate = [&](float mc, float& total, bool with_dma) __attribute__((always_inline)) {
+            float ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) mxa[j] = fmaxf(s[0][j], s[1][j]);
+            for (int kb = 0; kb < 2; ++kb) {
+                if (with_dma && dma_t >= 0) {
+                    if (kb == 0) dma_slot(dma_t, 0);
+                    if (NDMA == 2) { dma_slot(dma_t, 1 + kb); if (kb == 1) dma_slot(dma_t, 3); }
+                    else if (kb == 1) dma_slot(dma_t, 1);
+                }
+                unsigned pk[8];
 #pragma unroll
-        for (int r = 4; r < 16; r += 4)
+                for (int r = 0; r < 16; r += 2) {
+                    const float p0 = fast_exp2(fmaf(s[kb][r], c, -mc));
+                    const float p1 = fast_exp2(fmaf(s[kb][r + 1], c, -mc));
+                    ps[(r >> 1) & 3] += p0 + p1;
+                    pk[r >> 1] = pack_bf16x2(p0, p1);
+                }
+                const u32x4 lo = {pk[0], pk[1], pk[2], pk[3]}, hi = {pk[4], pk[5], pk[6], pk[7]};
+                pf[2 * kb] = __builtin_bit_cast(bf16x8, lo);
+                pf[2 * kb + 1] = __builtin_bit_cast(bf16x8, hi);
+            }
+            total = (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        };
+        float psum;
+        exponentiate((m_ref == -INFINITY ? 0.f : m_ref) * c, psum, true);
+        const bool redo = !(psum < kBig);                       // also true for inf and NaN
+        if (t == 0 || __builtin_amdgcn_ballot_w64(redo) != 0) {
+            // rare: one serial chain keeps the register need of this path low
+            float mx = s[0][0];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) mxa[j] = fmaxf(fmaxf(mxa[j], s[0][r + j]), s[1][r + j]);
-        float mx = fmaxf(fmaxf(mxa[0], mxa[1]), fmaxf(mxa[2], mxa[3]));
-        if (dma_t >= 0) dma_slot(dma_t, 0);
-        mx = max_across_halves(mx);
-        // raise the reference only when some row of this wavefront outgrew it by 2^kTau
-        const bool grow = (mx - m_ref) * c > kTau;           // false for NaN (-inf - -inf)
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
+            mx = max_across_halves(mx);
             const float m_new = fmaxf(m_ref, mx);
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = fast_exp2((m_ref - m_use) * c);
+            const float alpha = (m_ref == m_new) ? 1.0f : fast_exp2((m_ref - m_use) * c);   // -inf -> 0
             m_ref = m_new;
             l_run *= alpha;
 #pragma unroll
             for (int i = 0; i < DB; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+            exponentiate(m_use * c, psum, false);
         }
-        const float mc = (m_ref == -INFINITY ? 0.f : m_ref) * c;
-        float ps[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (dma_t >= 0) {
-                if (NDMA == 2) { dma_slot(dma_t, 1 + kb); if (kb == 1) dma_slot(dma_t, 3); }
-                else if (kb == 1) dma_slot(dma_t, 1);
-            }
-            unsigned pk[8];
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const float p0 = fast_exp2(fmaf(s[kb][r], c, -mc));
-                const float p1 = fast_exp2(fmaf(s[kb][r + 1], c, -mc));
-                ps[(r >> 1) & 3] += p0 + p1;
-                pk[r >> 1] = pack_bf16x2(p0, p1);
-            }
-            const u32x4 lo = {pk[0], pk[1], pk[2], pk[3]}, hi = {pk[4], pk[5], pk[6], pk[7]};
-            pf[2 * kb] = __builtin_bit_cast(bf16x8, lo);
-            pf[2 * kb + 1] = __builtin_bit_cast(bf16x8, hi);
-        }
-        l_run += (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        l_run += psum;
         __builtin_amdgcn_s_setprio(0);
     };
 

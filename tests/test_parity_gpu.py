@@ -65,6 +65,34 @@ def test_scale_other_than_rsqrt_d_and_null_lse():
     assert np.array_equal(o2, o) and np.isnan(lse2).all()      # lse untouched when NULL is passed
 
 
+@pytest.mark.parametrize("direction", ["rising", "falling", "spike"])
+@pytest.mark.parametrize("causal", [False, True])
+def test_scores_far_from_the_first_tile_maximum(direction, causal):
+    """The kernel exponentiates against a stale reference and only re-bases when a partial sum
+    would overflow: drive the scores hundreds of binades away from the first tile's maximum
+    (upwards: forces re-basing several times; downwards: everything after the first tiles
+    underflows against the reference; spike: one huge score in the middle of a late tile)."""
+    B, Hq, Hkv, S, D = 1, 2, 1, 1024, 128
+    rng = np.random.default_rng(77)
+    q = rng.standard_normal((B, Hq, S, D)).astype(np.float32)
+    k = rng.standard_normal((B, Hkv, S, D)).astype(np.float32)
+    v = rng.standard_normal((B, Hkv, S, D)).astype(np.float32)
+    u = np.ones(D, dtype=np.float32) / np.sqrt(D)
+    q = q + 40.0 * u                                 # every query has a large component along u
+    ramp = np.linspace(0.0, 1.0, S, dtype=np.float32)[None, None, :, None]
+    if direction == "rising":
+        k = k + 60.0 * ramp * u                      # q.k grows by ~2400 -> ~300 binades after scaling
+    elif direction == "falling":
+        k = k + 60.0 * (1.0 - ramp) * u
+    else:
+        k[:, :, 777, :] += 80.0 * u
+    qb, kb, vb = (I.f32_to_bf16_bits(x) for x in (q, k, v))
+    scale = D ** -0.5
+    o, lse = run_hip(qb, kb, vb, causal, scale)
+    o_ref, lse_ref = oracle_parallel(qb, kb, vb, causal, scale)
+    print(direction, causal, check(o, lse, o_ref, lse_ref, direction))
+
+
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
 def test_full_size_configs_sampled_rows(name):
     """The benchmark configurations at full size; the reference is evaluated on seeded

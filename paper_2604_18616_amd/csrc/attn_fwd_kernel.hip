@@ -318,7 +318,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
 // end of period T and published by the barrier that closes it.
 // ------------------------------------------------------------------------------------
 constexpr float kBig = 18446744073709551616.0f;   // 2^64: bound on a partial row sum of the fast path
-constexpr int kPF = 3;   // MFMA operands kept in flight from LDS (ring of 4-register fragments)
+// Tuning constants (overridable at compile time for A/B runs).
+#ifndef ATTN_PF
+#define ATTN_PF 3
+#endif
+#ifndef ATTN_SM_PRIO
+#define ATTN_SM_PRIO 2
+#endif
+constexpr int kPF = ATTN_PF;           // MFMA operands kept in flight from LDS (ring of 4-register fragments)
+constexpr int kSmPrio = ATTN_SM_PRIO;  // wave priority while in the softmax (0 elsewhere)
 
 template <int V> struct IntC { static constexpr int value = V; };
 // compile-time loop: f(IntC<I>{}) for I = BEGIN .. END-1, everything inlined
@@ -343,6 +351,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     constexpr int NQK = 2 * KS;                 // MFMAs of S^T = K Q^T per tile
 
     __shared__ __attribute__((aligned(1024))) char smem[4 * TB];   // K0 K1 V0 V1
+    __shared__ __attribute__((aligned(16))) char smem_o[8 * kWaveRows * D * 2];   // O staging, one 32 x D tile per wavefront
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -395,7 +404,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
         for (int n = 0; n < NDMA; ++n) dma_part(vh, vgoff, t, 2 + (t & 1), n);
     };
     auto dma_slot = [&](int t, int j) __attribute__((always_inline)) {
-        if (j < NDMA) dma_part(vh, vgoff, t, 2 + (t & 1), j);
+        if (j < NDMA) { if (t < nT) dma_part(vh, vgoff, t, 2 + (t & 1), j); }
         else if (t + 1 < nT) dma_part(kh, kgoff, t + 1, (t + 1) & 1, j - NDMA);
     };
     // vmcnt(0) only (expcnt/lgkmcnt fields left at their maxima).  The builtin, unlike
@@ -477,11 +486,14 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     auto prefetch_qk = [&](auto kbuf) __attribute__((always_inline)) {
         static_for<NPV, NPV + kPF>([&](auto ic) __attribute__((always_inline)) { fetch_op(kbuf, IntC<0>{}, ic); });
     };
-    auto mfma_run = [&](auto kbuf, auto vbuf, auto do_pv, auto do_qk, int dma_t) __attribute__((always_inline)) {
+    // do_pv is a compile-time switch (only the very first tile has no PV); qk_rt is a run-time,
+    // wavefront-uniform switch: the last MFMA phase of a wavefront (PV of its last tile) runs
+    // through the same code with the QK^T half branched over, so there is one instruction
+    // stream per buffer parity and no register shuffling between variants.
+    auto mfma_run = [&](auto kbuf, auto vbuf, auto do_pv, bool qk_rt, int dma_t) __attribute__((always_inline)) {
         constexpr int FIRST = decltype(do_pv)::value ? 0 : NPV;
-        constexpr int LAST = decltype(do_qk)::value ? NPV + NQK : NPV;
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<FIRST, LAST>([&](auto ic) __attribute__((always_inline)) {
+        constexpr int LAST = NPV + NQK;
+        auto one = [&](auto ic) __attribute__((always_inline)) {
             constexpr int i = decltype(ic)::value;
             if constexpr (i < NPV) {
                 constexpr int kk = i / DB, dblk = i % DB;
@@ -496,17 +508,21 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
                 }
             }
             if constexpr (i + kPF < LAST) fetch_op(kbuf, vbuf, IntC<i + kPF>{});
-            // loads of this phase pair, early in the stream: they must land before the phase ends
+            // loads of this period, early in the stream: they must land before the period ends
             constexpr int NSLOT = 2 * NDMA;
             if constexpr ((i - FIRST) % 2 == 1 && (i - FIRST) / 2 < NSLOT) {
                 if (dma_t >= 0) dma_slot(dma_t, (i - FIRST) / 2);
             }
             __builtin_amdgcn_sched_barrier(0);
-        });
+        };
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (decltype(do_pv)::value) static_for<0, NPV>(one);
+        if (qk_rt) static_for<NPV, NPV + NQK>(one);
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     auto softmax = [&](int t, int dma_t) __attribute__((always_inline)) {
-        __builtin_amdgcn_s_setprio(2);
+        __builtin_amdgcn_s_setprio(kSmPrio);
         const int key0 = t * kBc;
         if (key0 + kBc - 1 > wave_lim_min) {   // causal diagonal
             // key(kb, r) = key0 + 32*kb + 8*(r/4) + 4*half + r%4 is masked iff it exceeds lim:
@@ -587,13 +603,9 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
         issue_v(t);
         if (t + 1 < nT) issue_k(t + 1);
     };
-    auto mfma_phase = [&](auto kbuf, auto vbuf, auto do_pv, auto do_qk, int dma_t) __attribute__((always_inline)) {
+    auto mfma_phase = [&](auto kbuf, auto vbuf, auto do_pv, bool qk_rt, int dma_t) __attribute__((always_inline)) {
         if constexpr (decltype(do_pv)::value) prefetch_pv(vbuf); else prefetch_qk(kbuf);
-        mfma_run(kbuf, vbuf, do_pv, do_qk, dma_t);
-    };
-    auto pv_only = [&](int t, int dma_t) __attribute__((always_inline)) {   // PV(t), V(t) in buffer t & 1
-        if (t & 1) mfma_phase(IntC<0>{}, IntC<1>{}, IntC<1>{}, IntC<0>{}, dma_t);
-        else       mfma_phase(IntC<0>{}, IntC<0>{}, IntC<1>{}, IntC<0>{}, dma_t);
+        mfma_run(kbuf, vbuf, do_pv, qk_rt, dma_t);
     };
     // One barrier per tile period T.  In period T both groups read K(T) and V(T-1); the loads
     // of K(T+1) and V(T) are issued early in the period (their buffers were last read in
@@ -601,67 +613,72 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     //     group 0:  PV(T-1), QK(T) [MFMA stream]  then  softmax(T)
     //     group 1:  softmax(T-1)                  then  PV(T-1), QK(T) [MFMA stream]
     // so the two wavefronts of a SIMD start every period in opposite kinds of work and
-    // trade places without a barrier in between.
+    // trade places without a barrier in between.  A wavefront with nTw tiles runs periods
+    // 1 .. nTw with this code (in period nTw its QK and, for group 0, its softmax are switched
+    // off), then idles through the remaining periods of the workgroup; if nTw == nT its last
+    // PV comes after the last barrier.
     auto idle_tiles = [&](int t) __attribute__((always_inline)) {
         for (; t < nT; ++t) { loads(t); wait_loads(); phase_barrier(); }
     };
     if (nTw == 0) {
         idle_tiles(0);
     } else if (group == 0) {
-        mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, IntC<1>{}, 0);
+        mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, true, 0);
         softmax(0, -1);
         wait_loads();
         phase_barrier();
-        int t = 1;
+        // periods 1 .. nTw-1: everything on, no run-time switches in the hot loop
         auto step = [&](auto par, int tt) __attribute__((always_inline)) {
             constexpr int PAR = decltype(par)::value;
-            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, IntC<1>{}, tt);
+            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, true, tt);
             softmax(tt, -1);
             wait_loads();
             phase_barrier();
         };
+        // period nTw: only PV(nTw-1) is left for this wavefront
+        auto last = [&](auto par, int tt) __attribute__((always_inline)) {
+            constexpr int PAR = decltype(par)::value;
+            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, false, tt < nT ? tt : -1);
+            if (tt < nT) { wait_loads(); phase_barrier(); }
+        };
+        int t = 1;
         for (; t + 1 < nTw; t += 2) { step(IntC<1>{}, t); step(IntC<0>{}, t + 1); }
         if (t < nTw) { step(IntC<1>{}, t); ++t; }
-        if (t < nT) {
-            pv_only(t - 1, t);
-            wait_loads();
-            phase_barrier();
-            idle_tiles(t + 1);
-        } else {
-            pv_only(nT - 1, -1);
-        }
+        if (t & 1) last(IntC<1>{}, t); else last(IntC<0>{}, t);
+        idle_tiles(t + 1);
     } else {
         loads(0);
-        mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, IntC<1>{}, -1);
+        mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, true, -1);
         wait_loads();
         phase_barrier();
-        int t = 1;
         auto step = [&](auto par, int tt) __attribute__((always_inline)) {
             constexpr int PAR = decltype(par)::value;
             softmax(tt - 1, tt);
-            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, IntC<1>{}, -1);
+            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, true, -1);
             wait_loads();
             phase_barrier();
         };
+        auto last = [&](auto par, int tt) __attribute__((always_inline)) {
+            constexpr int PAR = decltype(par)::value;
+            softmax(tt - 1, tt < nT ? tt : -1);
+            mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, false, -1);
+            if (tt < nT) { wait_loads(); phase_barrier(); }
+        };
+        int t = 1;
         for (; t + 1 < nTw; t += 2) { step(IntC<1>{}, t); step(IntC<0>{}, t + 1); }
         if (t < nTw) { step(IntC<1>{}, t); ++t; }
-        if (t < nT) {
-            softmax(t - 1, t);
-            pv_only(t - 1, -1);
-            wait_loads();
-            phase_barrier();
-            idle_tiles(t + 1);
-        } else {
-            softmax(nT - 1, -1);
-            pv_only(nT - 1, -1);
-        }
+        if (t & 1) last(IntC<1>{}, t); else last(IntC<0>{}, t);
+        idle_tiles(t + 1);
     }
 
-    // ---- epilogue
+    // ---- epilogue: normalise, round once to bf16, transpose the wavefront's 32 x D tile of O
+    // through its own LDS staging area and store whole rows (16 bytes per lane, each store
+    // instruction writes 1 KB of contiguous output); LSE straight from registers.
     const float l_tot = sum_across_halves(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    if (qi < Sq) {
-        __bf16* orow = p.o + (((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq + qi) * D;
+    {
+        char* const stage = smem_o + wave * (kWaveRows * D * 2);
+        const int row = lane & 31;
 #pragma unroll
         for (int dblk = 0; dblk < DB; ++dblk)
 #pragma unroll
@@ -669,12 +686,21 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
                 u32x2 w;
                 w[0] = pack_bf16x2(oacc[dblk][4 * g4 + 0] * inv, oacc[dblk][4 * g4 + 1] * inv);
                 w[1] = pack_bf16x2(oacc[dblk][4 * g4 + 2] * inv, oacc[dblk][4 * g4 + 3] * inv);
-                *(u32x2*)(orow + o_d(lane, dblk, 4 * g4)) = w;
+                *(u32x2*)(stage + o_stage_offset<D>(row, o_d(lane, dblk, 4 * g4))) = w;
             }
-        if (p.lse != nullptr && half == 0) {
-            const float v = l_tot > 0.f ? m_ref * p.scale + logf(l_tot) : -INFINITY;
-            p.lse[((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq + qi] = v;
+        __bf16* const otile = p.o + (((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq + wrow0) * D;
+        constexpr int ROWS_PER_ST = 64 / CPR;
+#pragma unroll
+        for (int j = 0; j < kWaveRows / ROWS_PER_ST; ++j) {
+            const int r = j * ROWS_PER_ST + lane / CPR;
+            const int pos = lane % CPR;
+            const u32x4 val = *(const u32x4*)(stage + r * (D * 2) + pos * 16);
+            if (wrow0 + r < Sq) *(u32x4*)(otile + (size_t)r * D + o_stage_chunk<D>(r, pos) * 8) = val;
         }
+    }
+    if (qi < Sq && p.lse != nullptr && half == 0) {
+        const float v = l_tot > 0.f ? m_ref * p.scale + logf(l_tot) : -INFINITY;
+        p.lse[((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq + qi] = v;
     }
 }
 

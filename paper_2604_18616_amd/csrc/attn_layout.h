@@ -101,4 +101,13 @@ template <int D> ATTN_HD constexpr int pv_addr_offset(int lane, int dblk, int kk
 // Accumulator dblk, register r of lane l is O[query = l%32][d = 32*dblk + mfma_c_row(l, r)].
 ATTN_HD constexpr int o_d(int lane, int dblk, int r) { return 32 * dblk + mfma_c_row(lane, r); }
 
+// ---- O staging tile of one wavefront (epilogue transpose) ------------------------------
+// 32 rows x D bf16, rows of 16-byte chunks; logical chunk c of row r sits at chunk position
+// c ^ (r % chunks_per_row), so the 8-byte register writes (32 rows at one d) and the 16-byte
+// row reads are both conflict-free.
+template <int D> ATTN_HD constexpr int o_stage_offset(int row, int d) {
+    return row * (D * 2) + ((((d / 8) ^ (row % (D / 8)))) * kChunk) + 2 * (d % 8);
+}
+template <int D> ATTN_HD constexpr int o_stage_chunk(int row, int pos) { return pos ^ (row % (D / 8)); }
+
 }  // namespace attn_layout

@@ -114,7 +114,34 @@ template <int D> void check_banks() {
     }
 }
 
+// O staging tile: every (row, d) has its own bytes; the row reads recover whole rows.
+template <int D> void check_o_stage() {
+    std::vector<int> owner(32 * D * 2, -1);
+    for (int lane = 0; lane < 64; ++lane) for (int dblk = 0; dblk < D / 32; ++dblk) for (int g4 = 0; g4 < 4; ++g4) {
+        const int row = lane % 32, d0 = o_d(lane, dblk, 4 * g4);
+        const int off = o_stage_offset<D>(row, d0);
+        CHECK(off % 8 == 0 && off + 8 <= 32 * D * 2, "stage offset out of range");
+        for (int b = 0; b < 8; ++b) { CHECK(owner[off + b] < 0, "O stage byte written twice"); owner[off + b] = row * D + d0 + b / 2; }
+    }
+    constexpr int CPR = D / 8;
+    for (int j = 0; j < 32 / (64 / CPR); ++j) for (int lane = 0; lane < 64; ++lane) {
+        const int r = j * (64 / CPR) + lane / CPR, pos = lane % CPR;
+        const int d = o_stage_chunk<D>(r, pos) * 8;
+        for (int b = 0; b < 16; ++b) CHECK(owner[r * D * 2 + pos * 16 + b] == r * D + d + b / 2, "O stage read/write mismatch row %d pos %d", r, pos);
+    }
+    // bank model: the 8-byte writes of a half-wave (32 lanes = 32 rows at one d, same half) spread over 64 banks
+    for (int dblk = 0; dblk < D / 32; ++dblk) for (int g4 = 0; g4 < 4; ++g4) for (int half = 0; half < 2; ++half) {
+        std::set<int> banks;
+        for (int lane = 32 * half; lane < 32 * half + 32; ++lane) {
+            const int off = o_stage_offset<D>(lane % 32, o_d(lane, dblk, 4 * g4));
+            banks.insert(off / 4 % 64); banks.insert((off + 4) / 4 % 64);
+        }
+        CHECK((int)banks.size() >= (D == 128 ? 32 : 16), "O stage writes concentrate on %zu banks", banks.size());   // at most 2-way (D=128) / 4-way (D=64) conflicts; runs once per workgroup
+    }
+}
+
 int main() {
+    check_o_stage<128>(); check_o_stage<64>();
     check_qk<128>(false); check_qk<64>(false);
     check_qk<128>(true);  check_qk<64>(true);
     check_pv<128>(); check_pv<64>();

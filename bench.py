@@ -43,6 +43,10 @@ def read_traffic(workload: str):
     return None
 
 
+def prop_cus(torch, dev) -> int:
+    return torch.cuda.get_device_properties(dev).multi_processor_count
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,6 +119,18 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     kernel_ms = e0.elapsed_time(e1) / args.steps
 
+    # what this GPU sustains on nothing but bf16 MFMAs (same stream, same events)
+    sink = torch.zeros(16, dtype=torch.float32, device=dev)
+    cal_blocks, cal_iters = prop_cus(torch, dev), 20000
+    lib.attn_mfma_calibration(sink.data_ptr(), cal_blocks, 2000, sp)
+    torch.cuda.synchronize()
+    c0e, c1e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0e.record(stream)
+    cal_flops = lib.attn_mfma_calibration(sink.data_ptr(), cal_blocks, cal_iters, sp)
+    c1e.record(stream)
+    torch.cuda.synchronize()
+    mfma_sustained = cal_flops / (c0e.elapsed_time(c1e) * 1e-3) / 1e12 if cal_flops > 0 else None
+
     flops = lib.attn_fwd_flops(*dims, causal)
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kernel_ms * 1e-3) / 1e12
@@ -162,7 +178,8 @@ def main() -> int:
         "effective_tflops": w.dense_flops() / (ms_per_step * 1e-3) / 1e12,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": read_traffic(w.name),
-                     "kernel_ms": kernel_ms},
+                     "kernel_ms": kernel_ms, "mfma_sustained_tflops": mfma_sustained,
+                     "frac_of_sustained": (achieved / mfma_sustained) if mfma_sustained else None},
         "cpu_baseline": cpu,
         "parity": parity,
         "device": {"name": prop.name, "cus": prop.multi_processor_count},

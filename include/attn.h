@@ -78,6 +78,16 @@ int attn_version(void);
  */
 double attn_fwd_flops(int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal);
 
+/*
+ * Measurement aid (paper Section 7 measures kernels against the hardware's matrix
+ * throughput; the bench reports the published peak AND what this GPU sustains): enqueue
+ * `blocks` workgroups of 8 wavefronts that each issue 4*iters dense bf16 32x32x16 MFMAs and
+ * nothing else.  Returns the FLOPs performed (time it with events on `stream`), or -1.0 on
+ * bad arguments / refused launch.  `sink` is DEVICE memory of at least 4 bytes, never
+ * written in practice.  Asynchronous, allocates nothing.
+ */
+double attn_mfma_calibration(float *sink, int blocks, int iters, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -38,6 +38,11 @@ extern "C" int attn_fwd(const void* q, const void* k, const void* v, void* o, fl
     return attn_launch(p, D, causal != 0, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
+extern "C" double attn_mfma_calibration(float* sink, int blocks, int iters, void* stream) {
+    if (!sink || blocks <= 0 || iters <= 0) return -1.0;
+    return attn_launch_mfma_calibration(sink, blocks, iters, (hipStream_t)stream);
+}
+
 extern "C" const char* attn_strerror(int code) {
     switch (code) {
         case ATTN_OK:              return "success";

@@ -704,7 +704,38 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     }
 }
 
+// Calibration kernel: nothing but back-to-back v_mfma_f32_32x32x16_bf16 on four independent
+// accumulators per wavefront, two wavefronts per SIMD, operands that differ per lane and per
+// step.  Its rate is the MFMA throughput this GPU sustains at the clock it settles to under
+// matrix load, the practical ceiling next to the published peak.
+__global__ __launch_bounds__(512, 1) void mfma_calibration_kernel(float* sink, int iters) {
+    const int lane = threadIdx.x & 63;
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(0.25f + 0.001f * (float)((lane * 8 + e) % 97));
+        b[e] = (__bf16)(0.50f - 0.002f * (float)((lane * 5 + e) % 61));
+    }
+    f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+    for (int i = 0; i < iters; ++i) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, a, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, b, c3, 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t += c0[r] + c1[r] + c2[r] + c3[r];
+    if (t == 123456.789f) sink[0] = t;      // keeps the accumulators alive; never true in practice
+}
+
 }  // namespace
+
+double attn_launch_mfma_calibration(float* sink, int blocks, int iters, hipStream_t stream) {
+    hipLaunchKernelGGL(mfma_calibration_kernel, dim3((unsigned)blocks), dim3(512), 0, stream, sink, iters);
+    if (hipGetLastError() != hipSuccess) return -1.0;
+    return (double)blocks * 8.0 * (double)iters * 4.0 * 32768.0;   // 2*32*32*16 flop per MFMA
+}
 
 // Host-side launcher: the only symbol the C-ABI translation unit needs from this file.
 // Key counts that are a multiple of the 64-key tile take the ping-pong kernel (all its

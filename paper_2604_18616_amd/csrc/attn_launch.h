@@ -19,3 +19,7 @@ struct AttnParams {
 // Enqueue the forward kernel for head dimension D (64 or 128) on `stream`.
 // Returns 0, or -1 if the runtime refused the launch.
 int attn_launch(AttnParams p, int D, int causal, hipStream_t stream);
+
+// Enqueue the pure-MFMA calibration kernel (blocks x 8 wavefronts x iters x 4 MFMAs); returns
+// the FLOPs it performs, or -1 if the launch was refused.  sink: >= 4 bytes of device memory.
+double attn_launch_mfma_calibration(float* sink, int blocks, int iters, hipStream_t stream);

@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_header_declares_the_boundary():
     names = declared_functions()
-    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops"}
+    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops", "attn_mfma_calibration"}
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -72,6 +72,12 @@ def test_flops_helper_matches_workload_table(lib):
     assert lib.attn_fwd_flops(1, 1, 1, 3, 5, 64, 1) == 4 * 64 * (3 + 4 + 5)     # bottom-right aligned
     assert lib.attn_fwd_flops(1, 1, 1, 5, 3, 64, 1) == 4 * 64 * (0 + 0 + 1 + 2 + 3)
     assert lib.attn_fwd_flops(1, 3, 2, 4, 4, 64, 0) == -1.0
+
+
+def test_calibration_rejects_bad_arguments_without_a_gpu(lib):
+    assert lib.attn_mfma_calibration(None, 256, 10, None) == -1.0
+    assert lib.attn_mfma_calibration(A16, 0, 10, None) == -1.0
+    assert lib.attn_mfma_calibration(A16, 256, 0, None) == -1.0
 
 
 def test_python_binding_refuses_cpu_tensors():

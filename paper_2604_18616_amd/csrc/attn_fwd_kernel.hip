@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
 
 
 // ------------------------------------------------------------------------------------
-// Ping-pong kernel: Sk a multiple of 64.  512 threads = 8 wavefronts x 32 query rows
+// Ping-pong kernel (any Sk; RAGGED handles a partial last key tile).  512 threads = 8 wavefronts x 32 query rows
 // (Br = 256, as in the paper's Figure 1), Bc = 64.
 //
 // * K/V tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no staging
@@ -338,7 +338,7 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool RAGGED>
 __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;
@@ -391,9 +391,34 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     // slot j >= NDMA part j - NDMA of K(t+1).  Issued spread over the phase: a burst from all
     // eight wavefronts right after the barrier queues 32 KB of requests in front of the
     // address unit and stalls the issuing wavefronts.
+    // RAGGED (Sk not a multiple of 64): the last key tile t_rag has rows past Sk.  Their source
+    // row is clamped to Sk-1 (the copy must stay inside the tensor); K rows past Sk are masked
+    // by the softmax, V rows past Sk are zeroed in LDS by the wavefront that copied them, after
+    // its copy has landed and before the barrier that publishes the tile (0 * garbage must be 0).
+    const int t_rag = RAGGED ? Sk / kBc : -1;
     auto dma_part = [&](const __bf16* head, unsigned lane_off, int t, int buf, int n) __attribute__((always_inline)) {
+        const unsigned dst = lds_base + buf * TB + dma_dst_offset<D>(wave, n, 0);
+        if constexpr (RAGGED) {
+            if (t == t_rag) {
+                const int over = t * kBc + dma_row<D>(wave, n, lane) - (Sk - 1);
+                const unsigned off = (unsigned)((t * kBc + n * 8 * ROWS_PER_DMA) * (D * 2)) + lane_off
+                                     - (over > 0 ? (unsigned)(over * (D * 2)) : 0u);
+                dma_to_lds_16B(head, off, dst);
+                return;
+            }
+        }
         const __bf16* src = head + ((size_t)t * kBc + n * 8 * ROWS_PER_DMA) * D;
-        dma_to_lds_16B(src, lane_off, lds_base + buf * TB + dma_dst_offset<D>(wave, n, 0));
+        dma_to_lds_16B(src, lane_off, dst);
+    };
+    auto zero_ragged_v = [&](int t) __attribute__((always_inline)) {
+        if constexpr (RAGGED) {
+            if (t == t_rag) {
+#pragma unroll
+                for (int n = 0; n < NDMA; ++n)
+                    if (t * kBc + dma_row<D>(wave, n, lane) >= Sk)
+                        *(u32x4*)(smem + (2 + (t & 1)) * TB + dma_dst_offset<D>(wave, n, lane)) = u32x4{0u, 0u, 0u, 0u};
+            }
+        }
     };
     auto issue_k = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
@@ -599,6 +624,12 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     // parity: t = 0 (QK only), 1 <= t < nTw (both), t = nTw (PV only), t > nTw (this
     // wavefront is past its causal limit and only keeps the barriers and its share of the
     // loads).  Every path executes 2 barriers per tile plus one at the end.
+    // close period t: own loads (V(t), K(t+1)) have landed, ragged V rows are cleared, publish
+    auto end_period = [&](int t) __attribute__((always_inline)) {
+        wait_loads();
+        zero_ragged_v(t);
+        phase_barrier();
+    };
     auto loads = [&](int t) __attribute__((always_inline)) {
         issue_v(t);
         if (t + 1 < nT) issue_k(t + 1);
@@ -618,28 +649,26 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     // off), then idles through the remaining periods of the workgroup; if nTw == nT its last
     // PV comes after the last barrier.
     auto idle_tiles = [&](int t) __attribute__((always_inline)) {
-        for (; t < nT; ++t) { loads(t); wait_loads(); phase_barrier(); }
+        for (; t < nT; ++t) { loads(t); end_period(t); }
     };
     if (nTw == 0) {
         idle_tiles(0);
     } else if (group == 0) {
         mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, true, 0);
         softmax(0, -1);
-        wait_loads();
-        phase_barrier();
+        end_period(0);
         // periods 1 .. nTw-1: everything on, no run-time switches in the hot loop
         auto step = [&](auto par, int tt) __attribute__((always_inline)) {
             constexpr int PAR = decltype(par)::value;
             mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, true, tt);
             softmax(tt, -1);
-            wait_loads();
-            phase_barrier();
+            end_period(tt);
         };
         // period nTw: only PV(nTw-1) is left for this wavefront
         auto last = [&](auto par, int tt) __attribute__((always_inline)) {
             constexpr int PAR = decltype(par)::value;
             mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, false, tt < nT ? tt : -1);
-            if (tt < nT) { wait_loads(); phase_barrier(); }
+            if (tt < nT) end_period(tt);
         };
         int t = 1;
         for (; t + 1 < nTw; t += 2) { step(IntC<1>{}, t); step(IntC<0>{}, t + 1); }
@@ -649,20 +678,18 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     } else {
         loads(0);
         mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, true, -1);
-        wait_loads();
-        phase_barrier();
+        end_period(0);
         auto step = [&](auto par, int tt) __attribute__((always_inline)) {
             constexpr int PAR = decltype(par)::value;
             softmax(tt - 1, tt);
             mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, true, -1);
-            wait_loads();
-            phase_barrier();
+            end_period(tt);
         };
         auto last = [&](auto par, int tt) __attribute__((always_inline)) {
             constexpr int PAR = decltype(par)::value;
             softmax(tt - 1, tt < nT ? tt : -1);
             mfma_phase(IntC<PAR>{}, IntC<PAR ^ 1>{}, IntC<1>{}, false, -1);
-            if (tt < nT) { wait_loads(); phase_barrier(); }
+            if (tt < nT) end_period(tt);
         };
         int t = 1;
         for (; t + 1 < nTw; t += 2) { step(IntC<1>{}, t); step(IntC<0>{}, t + 1); }
@@ -738,22 +765,31 @@ double attn_launch_mfma_calibration(float* sink, int blocks, int iters, hipStrea
 }
 
 // Host-side launcher: the only symbol the C-ABI translation unit needs from this file.
-// Key counts that are a multiple of the 64-key tile take the ping-pong kernel (all its
-// loads are in bounds by construction); anything else takes the generic kernel.
+// The ping-pong kernel takes everything except tiny query counts (Sq <= 64: the generic
+// kernel's 128-row workgroups fit two per CU) and ragged key counts whose per-head byte size
+// does not fit the 32-bit offset the ragged tile's copy uses.
 int attn_launch(AttnParams p, int D, int causal, hipStream_t stream) {
-    const bool fast = (p.Sk % 64 == 0);
+    const bool ragged = (p.Sk % 64 != 0);
+    const bool fast = p.Sq > 64 && (!ragged || (long long)p.Sk * D * 2 < (1LL << 32));
     const int br = fast ? 256 : 128;
     p.nQt = (p.Sq + br - 1) / br;
     p.nblocks = p.B * p.Hq * p.nQt;
     const dim3 grid((unsigned)p.nblocks), block(fast ? 512 : 256);
-#define ATTN_LAUNCH(KERNEL, DD, CC) hipLaunchKernelGGL((KERNEL<DD, CC>), grid, block, 0, stream, p)
+#define ATTN_LAUNCH_PP(DD, CC, RR) hipLaunchKernelGGL((attn_fwd_pingpong<DD, CC, RR>), grid, block, 0, stream, p)
+#define ATTN_LAUNCH_GEN(DD, CC) hipLaunchKernelGGL((attn_fwd_generic<DD, CC>), grid, block, 0, stream, p)
     if (fast) {
-        if (D == 128) { if (causal) ATTN_LAUNCH(attn_fwd_pingpong, 128, true); else ATTN_LAUNCH(attn_fwd_pingpong, 128, false); }
-        else          { if (causal) ATTN_LAUNCH(attn_fwd_pingpong, 64, true);  else ATTN_LAUNCH(attn_fwd_pingpong, 64, false); }
+        if (D == 128) {
+            if (causal) { if (ragged) ATTN_LAUNCH_PP(128, true, true); else ATTN_LAUNCH_PP(128, true, false); }
+            else        { if (ragged) ATTN_LAUNCH_PP(128, false, true); else ATTN_LAUNCH_PP(128, false, false); }
+        } else {
+            if (causal) { if (ragged) ATTN_LAUNCH_PP(64, true, true); else ATTN_LAUNCH_PP(64, true, false); }
+            else        { if (ragged) ATTN_LAUNCH_PP(64, false, true); else ATTN_LAUNCH_PP(64, false, false); }
+        }
     } else {
-        if (D == 128) { if (causal) ATTN_LAUNCH(attn_fwd_generic, 128, true); else ATTN_LAUNCH(attn_fwd_generic, 128, false); }
-        else          { if (causal) ATTN_LAUNCH(attn_fwd_generic, 64, true);  else ATTN_LAUNCH(attn_fwd_generic, 64, false); }
+        if (D == 128) { if (causal) ATTN_LAUNCH_GEN(128, true); else ATTN_LAUNCH_GEN(128, false); }
+        else          { if (causal) ATTN_LAUNCH_GEN(64, true);  else ATTN_LAUNCH_GEN(64, false); }
     }
-#undef ATTN_LAUNCH
+#undef ATTN_LAUNCH_PP
+#undef ATTN_LAUNCH_GEN
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }

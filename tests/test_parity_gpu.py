@@ -34,6 +34,13 @@ SMALL_CASES = [
     # shifted keys stress the max subtraction (large common offset in every score of a row)
     small("shifted_keys", 1, 4, 4, 256, 640, 64, False, 23, sigma=0.5, k_shift=True),
     small("gqa8", 1, 8, 1, 256, 256, 128, True, 24),
+    # ragged key counts through the 256-row kernel (Sq > 64): partial last tile, fewer keys than a tile
+    small("ragged_keys_lt_tile", 1, 4, 2, 300, 37, 128, False, 25),
+    small("ragged_keys_tile_plus_one", 2, 2, 1, 130, 65, 64, False, 26),
+    small("ragged_keys_causal_long", 1, 4, 1, 700, 1000, 128, True, 27),
+    small("ragged_keys_causal_d64", 1, 4, 2, 513, 449, 64, True, 28),
+    small("ragged_both_noncausal", 2, 3, 3, 1001, 1003, 128, False, 29),
+    small("queries_65", 1, 2, 2, 65, 320, 128, True, 30),
 ]
 
 

@@ -65,6 +65,22 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
              int B, int Hq, int Hkv, int Sq, int Sk, int D,
              int causal, float scale, void *stream);
 
+/*
+ * The same operation on tensors with arbitrary batch / head / row strides (the paper's own
+ * kernel, Figure 1, takes Q, K, V, O as [seq, head, d]; a [B, S, H, D] buffer is
+ * strides {S*H*D, D, H*D}).  Each *_strides points to 3 HOST integers {batch, head, row}
+ * in ELEMENTS; the D elements of a row are contiguous.  Every stride must be a multiple of
+ * 8 elements (rows stay 16-byte aligned), row stride >= D and < 2^28, none negative; o must
+ * not overlap itself or the inputs.  lse is always contiguous [B, Hq, Sq].  Everything else
+ * (checks, error codes, asynchrony) is as for attn_fwd; ATTN_ERR_NULL_PTR also covers a NULL
+ * stride pointer, ATTN_ERR_MISALIGNED a stride that is not a multiple of 8.
+ */
+int attn_fwd_strided(const void *q, const void *k, const void *v, void *o, float *lse,
+                     int B, int Hq, int Hkv, int Sq, int Sk, int D,
+                     const long long *q_strides, const long long *k_strides,
+                     const long long *v_strides, const long long *o_strides,
+                     int causal, float scale, void *stream);
+
 /* Static, never-freed description of a return code of this library. */
 const char *attn_strerror(int code);
 

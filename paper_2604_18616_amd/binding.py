@@ -33,6 +33,8 @@ def load_library(build_if_missing: bool = True):
         i, f, p = ctypes.c_int, ctypes.c_float, ctypes.c_void_p
         lib.attn_fwd.restype = i
         lib.attn_fwd.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, f, p]
+        lib.attn_fwd_strided.restype = i
+        lib.attn_fwd_strided.argtypes = [p, p, p, p, p, i, i, i, i, i, i, p, p, p, p, i, f, p]
         lib.attn_strerror.restype = ctypes.c_char_p
         lib.attn_strerror.argtypes = [i]
         lib.attn_version.restype = i
@@ -63,33 +65,48 @@ def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, cau
                                    int(bool(causal)), float(scale), stream_ptr)
 
 
+def _strides3(t):
+    return (ctypes.c_longlong * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+
 def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
     """O, LSE = attention forward of bf16 CUDA tensors q [B,Hq,Sq,D], k/v [B,Hkv,Sk,D].
 
-    o (bf16 [B,Hq,Sq,D]) and lse (fp32 [B,Hq,Sq]) are allocated with torch if not given.
-    The kernel is enqueued on `stream` (default: torch's current stream); no sync.
+    The tensors may be strided views (e.g. a [B,S,H,D] buffer transposed to [B,H,S,D]) as long
+    as the last dimension is contiguous; contiguous inputs take attn_fwd, anything else
+    attn_fwd_strided.  o (bf16, q's shape) and lse (fp32 [B,Hq,Sq], contiguous) are allocated
+    with torch if not given.  The kernel is enqueued on `stream` (default: torch's current
+    stream); no sync.
     """
     import torch
 
     if not (q.is_cuda and k.is_cuda and v.is_cuda):
         raise ValueError("q, k, v must be CUDA tensors: there is no CPU path")
     for t in (q, k, v):
-        if t.dtype != torch.bfloat16 or not t.is_contiguous() or t.dim() != 4:
-            raise ValueError("q, k, v must be contiguous 4-D bfloat16 tensors")
+        if t.dtype != torch.bfloat16 or t.dim() != 4 or t.stride(3) != 1:
+            raise ValueError("q, k, v must be 4-D bfloat16 tensors with a contiguous last dimension")
     B, Hq, Sq, D = q.shape
     Bk, Hkv, Sk, Dk = k.shape
     if v.shape != k.shape or Bk != B or Dk != D:
         raise ValueError("inconsistent q/k/v shapes")
     if o is None:
-        o = torch.empty_like(q)
+        o = torch.empty_like(q)          # keeps q's layout for dense views
+    if o.shape != q.shape or o.dtype != torch.bfloat16 or o.stride(3) != 1:
+        raise ValueError("o must be bfloat16 with q's shape and a contiguous last dimension")
     if lse is None:
         lse = torch.empty((B, Hq, Sq), dtype=torch.float32, device=q.device)
     if scale is None:
         scale = float(D) ** -0.5
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
-    rc = attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
-                      B, Hq, Hkv, Sq, Sk, D, causal, scale, stream.cuda_stream)
+    lib = load_library()
+    if all(t.is_contiguous() for t in (q, k, v, o)):
+        rc = lib.attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                          B, Hq, Hkv, Sq, Sk, D, int(bool(causal)), float(scale), stream.cuda_stream)
+    else:
+        rc = lib.attn_fwd_strided(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                  B, Hq, Hkv, Sq, Sk, D, _strides3(q), _strides3(k), _strides3(v), _strides3(o),
+                                  int(bool(causal)), float(scale), stream.cuda_stream)
     if rc != 0:
         raise AttnError(rc, strerror(rc))
     return o, lse

@@ -15,9 +15,11 @@ static int check_dims(int B, int Hq, int Hkv, int Sq, int Sk, int D) {
     return ATTN_OK;
 }
 
-extern "C" int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                        int B, int Hq, int Hkv, int Sq, int Sk, int D,
-                        int causal, float scale, void* stream) {
+// Common path of both entry points.  Strides are in elements: {batch, head, row}.
+static int attn_fwd_impl(const void* q, const void* k, const void* v, void* o, float* lse,
+                         int B, int Hq, int Hkv, int Sq, int Sk, int D,
+                         const long long* qs, const long long* ks, const long long* vs, const long long* os,
+                         int causal, float scale, void* stream) {
     if (!q || !k || !v || !o) return ATTN_ERR_NULL_PTR;
     if (int rc = check_dims(B, Hq, Hkv, Sq, Sk, D)) return rc;
     if (D != 64 && D != 128) return ATTN_ERR_UNSUPPORTED;
@@ -26,16 +28,45 @@ extern "C" int attn_fwd(const void* q, const void* k, const void* v, void* o, fl
     if (nblocks >= (1LL << 31)) return ATTN_ERR_BAD_SHAPE;
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15u) return ATTN_ERR_MISALIGNED;
     if (lse && ((uintptr_t)lse & 3u)) return ATTN_ERR_MISALIGNED;
+    const long long* all[4] = {qs, ks, vs, os};
+    for (int t = 0; t < 4; ++t) {
+        if (all[t][2] < D || all[t][0] < 0 || all[t][1] < 0) return ATTN_ERR_BAD_SHAPE;     // rows may not overlap
+        if ((all[t][0] | all[t][1] | all[t][2]) & 7) return ATTN_ERR_MISALIGNED;            // keep every row 16-byte aligned
+        if (all[t][2] >= (1LL << 28)) return ATTN_ERR_BAD_SHAPE;
+    }
     if (!(scale > 0.0f) || isinf(scale)) return ATTN_ERR_BAD_SCALE;   // rejects NaN, <= 0, inf
 
     AttnParams p;
     p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v;
     p.o = (__bf16*)o; p.lse = lse;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.Sq = Sq; p.Sk = Sk;
+    p.q_sb = qs[0]; p.q_sh = qs[1]; p.q_ss = qs[2];
+    p.k_sb = ks[0]; p.k_sh = ks[1]; p.k_ss = ks[2];
+    p.v_sb = vs[0]; p.v_sh = vs[1]; p.v_ss = vs[2];
+    p.o_sb = os[0]; p.o_sh = os[1]; p.o_ss = os[2];
     p.nQt = 0; p.nblocks = 0;   // set by the launcher
     p.scale = scale;
     p.scale_log2 = (float)((double)scale * 1.4426950408889634074);
     return attn_launch(p, D, causal != 0, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                        int B, int Hq, int Hkv, int Sq, int Sk, int D,
+                        int causal, float scale, void* stream) {
+    if (int rc = check_dims(B, Hq, Hkv, Sq, Sk, D)) return (q && k && v && o) ? rc : ATTN_ERR_NULL_PTR;
+    const long long qs[3] = {(long long)Hq * Sq * D, (long long)Sq * D, D};
+    const long long ks[3] = {(long long)Hkv * Sk * D, (long long)Sk * D, D};
+    return attn_fwd_impl(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, qs, ks, ks, qs, causal, scale, stream);
+}
+
+extern "C" int attn_fwd_strided(const void* q, const void* k, const void* v, void* o, float* lse,
+                                int B, int Hq, int Hkv, int Sq, int Sk, int D,
+                                const long long* q_strides, const long long* k_strides,
+                                const long long* v_strides, const long long* o_strides,
+                                int causal, float scale, void* stream) {
+    if (!q_strides || !k_strides || !v_strides || !o_strides) return ATTN_ERR_NULL_PTR;
+    return attn_fwd_impl(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, q_strides, k_strides, v_strides, o_strides,
+                         causal, scale, stream);
 }
 
 extern "C" double attn_mfma_calibration(float* sink, int blocks, int iters, void* stream) {

@@ -122,9 +122,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
     const int Sq = p.Sq, Sk = p.Sk;
     const int shift = Sk - Sq;                 // causal: key j visible to query i iff j <= i + shift
 
-    const __bf16* qh = p.q + ((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq * D;
-    const __bf16* kh = p.k + ((size_t)bc.b * p.Hkv + bc.hk) * (size_t)Sk * D;
-    const __bf16* vh = p.v + ((size_t)bc.b * p.Hkv + bc.hk) * (size_t)Sk * D;
+    const __bf16* qh = p.q + bc.b * p.q_sb + bc.hq * p.q_sh;
+    const __bf16* kh = p.k + bc.b * p.k_sb + bc.hk * p.k_sh;
+    const __bf16* vh = p.v + bc.b * p.v_sb + bc.hk * p.v_sh;
 
     // number of key tiles this workgroup visits
     int nT;
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
     // Q^T B-operand fragments: Q[qi][16*ks + 8*half .. +7], rows past Sq clamped (never stored)
     bf16x8 qf[KS];
     {
-        const __bf16* qrow = qh + (size_t)min(qi, Sq - 1) * D + 8 * half;
+        const __bf16* qrow = qh + (long long)min(qi, Sq - 1) * p.q_ss + 8 * half;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qrow + 16 * ks);
     }
@@ -167,8 +167,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
             const int row = idx / CPR, ch = idx % CPR;
             const int key = t * kBc + row;
             if (key < Sk) {
-                kreg[n] = *(const u32x4*)(kh + (size_t)key * D + ch * 8);
-                vreg[n] = *(const u32x4*)(vh + (size_t)key * D + ch * 8);
+                kreg[n] = *(const u32x4*)(kh + (long long)key * p.k_ss + ch * 8);
+                vreg[n] = *(const u32x4*)(vh + (long long)key * p.v_ss + ch * 8);
             } else {
                 kreg[n] = u32x4{0, 0, 0, 0};
                 vreg[n] = u32x4{0, 0, 0, 0};
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
     const float l_tot = sum_across_halves(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     if (qi < Sq) {
-        __bf16* orow = p.o + (((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq + qi) * D;
+        __bf16* orow = p.o + bc.b * p.o_sb + bc.hq * p.o_sh + (long long)qi * p.o_ss;
 #pragma unroll
         for (int dblk = 0; dblk < DB; ++dblk)
 #pragma unroll
@@ -364,9 +364,9 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     const int Sq = p.Sq, Sk = p.Sk;
     const int shift = Sk - Sq;
 
-    const __bf16* qh = p.q + ((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq * D;
-    const __bf16* kh = p.k + ((size_t)bc.b * p.Hkv + bc.hk) * (size_t)Sk * D;
-    const __bf16* vh = p.v + ((size_t)bc.b * p.Hkv + bc.hk) * (size_t)Sk * D;
+    const __bf16* qh = p.q + bc.b * p.q_sb + bc.hq * p.q_sh;
+    const __bf16* kh = p.k + bc.b * p.k_sb + bc.hk * p.k_sh;
+    const __bf16* vh = p.v + bc.b * p.v_sb + bc.hk * p.v_sh;
 
     // tiles visited by the workgroup / by this wavefront
     int nT, nTw;
@@ -384,8 +384,11 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
 
     // Per-lane source byte offset of this wavefront's direct-to-LDS loads within a tile
     // (load n = 0; load n adds the constant 8 * ROWS_PER_DMA rows, folded into the base).
-    const unsigned kgoff = 2u * dma_src_elem<D, false>(wave, 0, lane);
-    const unsigned vgoff = 2u * dma_src_elem<D, true>(wave, 0, lane);
+    // Row pitches in bytes.  The launcher only picks this kernel when a whole head of K and of V
+    // spans less than 4 GiB, so every byte offset within a head fits 32 bits.
+    const unsigned k_rb = 2u * (unsigned)p.k_ss, v_rb = 2u * (unsigned)p.v_ss;
+    const unsigned kgoff = (unsigned)dma_row<D>(wave, 0, lane) * k_rb + 2u * (unsigned)(dma_src_elem<D, false>(wave, 0, lane) % D);
+    const unsigned vgoff = (unsigned)dma_row<D>(wave, 0, lane) * v_rb + 2u * (unsigned)(dma_src_elem<D, true>(wave, 0, lane) % D);
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
     // The loads of one phase pair, one instruction at a time: slot j < NDMA is part j of V(t),
     // slot j >= NDMA part j - NDMA of K(t+1).  Issued spread over the phase: a burst from all
@@ -396,19 +399,18 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     // by the softmax, V rows past Sk are zeroed in LDS by the wavefront that copied them, after
     // its copy has landed and before the barrier that publishes the tile (0 * garbage must be 0).
     const int t_rag = RAGGED ? Sk / kBc : -1;
-    auto dma_part = [&](const __bf16* head, unsigned lane_off, int t, int buf, int n) __attribute__((always_inline)) {
+    auto dma_part = [&](const __bf16* head, unsigned row_bytes, unsigned lane_off, int t, int buf, int n) __attribute__((always_inline)) {
         const unsigned dst = lds_base + buf * TB + dma_dst_offset<D>(wave, n, 0);
+        const unsigned tile_off = (unsigned)(t * kBc + n * 8 * ROWS_PER_DMA) * row_bytes;   // wavefront-uniform
         if constexpr (RAGGED) {
             if (t == t_rag) {
                 const int over = t * kBc + dma_row<D>(wave, n, lane) - (Sk - 1);
-                const unsigned off = (unsigned)((t * kBc + n * 8 * ROWS_PER_DMA) * (D * 2)) + lane_off
-                                     - (over > 0 ? (unsigned)(over * (D * 2)) : 0u);
+                const unsigned off = tile_off + lane_off - (over > 0 ? (unsigned)over * row_bytes : 0u);
                 dma_to_lds_16B(head, off, dst);
                 return;
             }
         }
-        const __bf16* src = head + ((size_t)t * kBc + n * 8 * ROWS_PER_DMA) * D;
-        dma_to_lds_16B(src, lane_off, dst);
+        dma_to_lds_16B((const __bf16*)((const char*)head + tile_off), lane_off, dst);
     };
     auto zero_ragged_v = [&](int t) __attribute__((always_inline)) {
         if constexpr (RAGGED) {
@@ -422,15 +424,15 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     };
     auto issue_k = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
-        for (int n = 0; n < NDMA; ++n) dma_part(kh, kgoff, t, t & 1, n);
+        for (int n = 0; n < NDMA; ++n) dma_part(kh, k_rb, kgoff, t, t & 1, n);
     };
     auto issue_v = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
-        for (int n = 0; n < NDMA; ++n) dma_part(vh, vgoff, t, 2 + (t & 1), n);
+        for (int n = 0; n < NDMA; ++n) dma_part(vh, v_rb, vgoff, t, 2 + (t & 1), n);
     };
     auto dma_slot = [&](int t, int j) __attribute__((always_inline)) {
-        if (j < NDMA) { if (t < nT) dma_part(vh, vgoff, t, 2 + (t & 1), j); }
-        else if (t + 1 < nT) dma_part(kh, kgoff, t + 1, (t + 1) & 1, j - NDMA);
+        if (j < NDMA) { if (t < nT) dma_part(vh, v_rb, vgoff, t, 2 + (t & 1), j); }
+        else if (t + 1 < nT) dma_part(kh, k_rb, kgoff, t + 1, (t + 1) & 1, j - NDMA);
     };
     // vmcnt(0) only (expcnt/lgkmcnt fields left at their maxima).  The builtin, unlike
     // inline asm, also tells the compiler that its own earlier global loads have landed.
@@ -460,7 +462,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     // Q^T B-operand fragments
     bf16x8 qf[KS];
     {
-        const __bf16* qrow = qh + (size_t)min(qi, Sq - 1) * D + 8 * half;
+        const __bf16* qrow = qh + (long long)min(qi, Sq - 1) * p.q_ss + 8 * half;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qrow + 16 * ks);
     }
@@ -715,14 +717,14 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
                 w[1] = pack_bf16x2(oacc[dblk][4 * g4 + 2] * inv, oacc[dblk][4 * g4 + 3] * inv);
                 *(u32x2*)(stage + o_stage_offset<D>(row, o_d(lane, dblk, 4 * g4))) = w;
             }
-        __bf16* const otile = p.o + (((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq + wrow0) * D;
+        __bf16* const otile = p.o + bc.b * p.o_sb + bc.hq * p.o_sh + (long long)wrow0 * p.o_ss;
         constexpr int ROWS_PER_ST = 64 / CPR;
 #pragma unroll
         for (int j = 0; j < kWaveRows / ROWS_PER_ST; ++j) {
             const int r = j * ROWS_PER_ST + lane / CPR;
             const int pos = lane % CPR;
             const u32x4 val = *(const u32x4*)(stage + r * (D * 2) + pos * 16);
-            if (wrow0 + r < Sq) *(u32x4*)(otile + (size_t)r * D + o_stage_chunk<D>(r, pos) * 8) = val;
+            if (wrow0 + r < Sq) *(u32x4*)(otile + (long long)r * p.o_ss + o_stage_chunk<D>(r, pos) * 8) = val;
         }
     }
     if (qi < Sq && p.lse != nullptr && half == 0) {
@@ -767,10 +769,11 @@ double attn_launch_mfma_calibration(float* sink, int blocks, int iters, hipStrea
 // Host-side launcher: the only symbol the C-ABI translation unit needs from this file.
 // The ping-pong kernel takes everything except tiny query counts (Sq <= 64: the generic
 // kernel's 128-row workgroups fit two per CU) and ragged key counts whose per-head byte size
-// does not fit the 32-bit offset the ragged tile's copy uses.
+// (or huge row strides) do not fit the 32-bit offsets the tile copies use.
 int attn_launch(AttnParams p, int D, int causal, hipStream_t stream) {
     const bool ragged = (p.Sk % 64 != 0);
-    const bool fast = p.Sq > 64 && (!ragged || (long long)p.Sk * D * 2 < (1LL << 32));
+    const long long kv_ss = p.k_ss > p.v_ss ? p.k_ss : p.v_ss;
+    const bool fast = p.Sq > 64 && ((long long)p.Sk + 64) * kv_ss * 2 < (1LL << 32);   // a head of K or V (padded to whole tiles) under 4 GiB
     const int br = fast ? 256 : 128;
     p.nQt = (p.Sq + br - 1) / br;
     p.nblocks = p.B * p.Hq * p.nQt;

@@ -10,6 +10,8 @@ struct AttnParams {
     __bf16* o;
     float* lse;        // may be null
     int B, Hq, Hkv, Sq, Sk;
+    // element strides: batch, head, sequence row (the D elements of a row are contiguous)
+    long long q_sb, q_sh, q_ss, k_sb, k_sh, k_ss, v_sb, v_sh, v_ss, o_sb, o_sh, o_ss;
     int nQt;           // query tiles per head (set by the launcher for the kernel it picks)
     int nblocks;       // B * Hq * nQt  (set by the launcher)
     float scale;       // multiplier on q.k before the softmax

@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_header_declares_the_boundary():
     names = declared_functions()
-    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops", "attn_mfma_calibration"}
+    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops", "attn_mfma_calibration", "attn_fwd_strided"}
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -64,6 +64,25 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
         assert call(lib, **kw) == -4, kw
     for s in (0.0, -0.5, math.nan, math.inf, -math.inf):
         assert call(lib, scale=s) == -5, s
+
+
+def test_strided_entry_point_argument_errors(lib):
+    L3 = ctypes.c_longlong * 3
+    good_q, good_k = L3(4 * 128 * 128, 128 * 128, 128), L3(2 * 128 * 128, 128 * 128, 128)
+
+    def scall(qs=good_q, ks=good_k, vs=good_k, os_=good_q, **kw):
+        a = dict(q=A16, k=A16, v=A16, o=A16, lse=A16, B=1, Hq=4, Hkv=2, Sq=128, Sk=128, D=128, causal=1, scale=0.1)
+        a.update(kw)
+        return lib.attn_fwd_strided(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["Hq"], a["Hkv"], a["Sq"], a["Sk"],
+                                    a["D"], qs, ks, vs, os_, a["causal"], a["scale"], None)
+
+    assert scall(qs=None) == -1 and scall(os_=None) == -1 and scall(q=None) == -1
+    assert scall(qs=L3(0, 128 * 128, 64)) == -2            # row stride smaller than D: rows overlap
+    assert scall(ks=L3(-8, 128 * 128, 128)) == -2
+    assert scall(vs=L3(0, 128 * 128, 1 << 28)) == -2
+    assert scall(qs=L3(4 * 128 * 128, 128 * 128, 132)) == -4   # not a multiple of 8 elements
+    assert scall(os_=L3(4, 128 * 128, 128)) == -4
+    assert scall(D=96) == -3 and scall(scale=0.0) == -5 and scall(Hq=3) == -2
 
 
 def test_flops_helper_matches_workload_table(lib):

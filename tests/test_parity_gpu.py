@@ -72,6 +72,33 @@ def test_scale_other_than_rsqrt_d_and_null_lse():
     assert np.array_equal(o2, o) and np.isnan(lse2).all()      # lse untouched when NULL is passed
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("D,Sq,Sk", [(128, 300, 300), (64, 200, 333), (128, 40, 130)])
+def test_strided_layout_of_the_papers_kernel(D, Sq, Sk, causal):
+    """attn_fwd_strided on [B, S, H, D] buffers (the [seq, head, d] layout of the paper's
+    Figure 1 with a batch dimension), output written in the same layout, plus a padded row
+    stride; compared with the reference on the equivalent [B, H, S, D] arrays."""
+    import torch
+    from paper_2604_18616_amd import binding
+    B, Hq, Hkv = 2, 4, 2
+    w = small("strided", B, Hq, Hkv, Sq, Sk, D, causal, 41)
+    qb, kb, vb = I.make_qkv(w)                                   # [B,H,S,D]
+    dev = lambda a: torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+    q_bshd = dev(np.ascontiguousarray(qb.transpose(0, 2, 1, 3)))  # [B,S,H,D] storage
+    k_bshd = dev(np.ascontiguousarray(kb.transpose(0, 2, 1, 3)))
+    pad = torch.full((B, Hkv, Sk, D + 16), float("nan"), dtype=torch.bfloat16, device="cuda")   # padded rows for V
+    pad[..., :D] = dev(vb)
+    o_bshd = torch.full((B, Sq, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+    binding.attn_fwd(q_bshd.transpose(1, 2), k_bshd.transpose(1, 2), pad[..., :D], o_bshd.transpose(1, 2), lse,
+                     causal=causal, scale=w.scale)
+    torch.cuda.synchronize()
+    o = I.bf16_bits_to_f32(o_bshd.transpose(1, 2).contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+    o_ref, lse_ref = oracle_parallel(qb, kb, vb, causal, w.scale)
+    print(check(o, lse.cpu().numpy().astype(np.float64), o_ref, lse_ref, "strided"))
+    assert torch.isnan(pad[..., D:].float()).all()              # padding untouched
+
+
 @pytest.mark.parametrize("direction", ["rising", "falling", "spike"])
 @pytest.mark.parametrize("causal", [False, True])
 def test_scores_far_from_the_first_tile_maximum(direction, causal):

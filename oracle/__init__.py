@@ -1,10 +1,11 @@
-"""fp64 CPU reference for attention forward -- TEST INFRASTRUCTURE, not the product.
+"""fp64 CPU references -- TEST INFRASTRUCTURE, not the product.
 
-Thin ctypes binding of ``attn_ref.c`` (the plain definition of Section 2 of the
+Thin ctypes bindings of ``attn_ref.c`` (the plain definition of Section 2 of the
 paper: S = Q K^T, P = softmax(S), O = P V, plus scale, GQA, causal mask and LSE as
-the library boundary states them).  Only ``tests/``, ``__graft_entry__.smoke()``
-and the ``cpu_baseline`` leg of ``bench.py`` may import this package; the product
-package never does.  Nothing here touches a GPU or the HIP library.
+the library boundary states them) and of ``gemm_ref.c`` (the bf16 matrix product of
+the paper's GEMM workload, Section 8, as three nested loops).  Only ``tests/``,
+``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import this
+package; the product package never does.  Nothing here touches a GPU or the HIP library.
 """
 from __future__ import annotations
 
@@ -17,17 +18,25 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "attn_ref.c")
 _LIB = os.path.join(_HERE, "liboracle_attn.so")
+_GEMM_SRC = os.path.join(_HERE, "gemm_ref.c")
+_GEMM_LIB = os.path.join(_HERE, "liboracle_gemm.so")
 _lib = None
+_gemm_lib = None
+
+
+def _compile(src: str, lib: str, force: bool) -> str:
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+        tmp = lib + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", tmp, src, "-lm"])
+        os.replace(tmp, lib)
+    return lib
 
 
 def build(force: bool = False) -> str:
-    """Compile attn_ref.c with gcc (plain -O2, no fast-math) and return the .so path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
-                               "-o", tmp, _SRC, "-lm"])
-        os.replace(tmp, _LIB)
-    return _LIB
+    """Compile the C references with gcc (plain -O2, no fast-math); returns the attention .so path."""
+    _compile(_GEMM_SRC, _GEMM_LIB, force)
+    return _compile(_SRC, _LIB, force)
 
 
 def _load():
@@ -109,3 +118,61 @@ def attn_ref_row_probs(q, k, v, causal: bool, scale: float, b: int, h: int, i: i
     if rc != 0:
         raise RuntimeError("attn_ref_row_probs failed with code %d" % rc)
     return probs, orow, float(lse[0])
+
+
+def _load_gemm():
+    global _gemm_lib
+    if _gemm_lib is None:
+        lib = ctypes.CDLL(_compile(_GEMM_SRC, _GEMM_LIB, False))
+        i, ll, p = ctypes.c_int, ctypes.c_longlong, ctypes.c_void_p
+        lib.gemm_ref_f64.restype = i
+        lib.gemm_ref_f64.argtypes = [p, p, p, p, i, i, i, ll, ll, i]
+        lib.gemm_ref_f64_samples.restype = i
+        lib.gemm_ref_f64_samples.argtypes = [p, p, p, p, i, p, p, i, i, i, ll, ll, i]
+        _gemm_lib = lib
+    return _gemm_lib
+
+
+def _gemm_dims(a, b, b_is_nk):
+    if a.dtype != np.uint16 or b.dtype != np.uint16 or a.ndim != 2 or b.ndim != 2:
+        raise TypeError("a, b must be 2-D uint16 arrays of bf16 bit patterns")
+    if a.strides[1] != 2 or b.strides[1] != 2 or a.strides[0] % 2 or b.strides[0] % 2:
+        raise ValueError("rows of a and b must be contiguous")
+    M, K = a.shape
+    N = b.shape[0] if b_is_nk else b.shape[1]
+    if (b.shape[1] if b_is_nk else b.shape[0]) != K:
+        raise ValueError("inner dimensions differ")
+    return M, N, K, a.strides[0] // 2, b.strides[0] // 2
+
+
+def gemm_ref(a, b, b_is_nk: bool = False):
+    """C = A B in fp64 and the absolute sums sum_k |a_ik||b_kj| (both [M,N]).
+
+    a [M,K], b [K,N] (or [N,K] if b_is_nk): uint16 arrays of bf16 bits; rows contiguous, row
+    pitch free (slices of wider arrays are fine).
+    """
+    lib = _load_gemm()
+    M, N, K, lda, ldb = _gemm_dims(a, b, b_is_nk)
+    c = np.empty((M, N), dtype=np.float64)
+    cabs = np.empty((M, N), dtype=np.float64)
+    rc = lib.gemm_ref_f64(_ptr(a), _ptr(b), _ptr(c), _ptr(cabs), M, N, K, lda, ldb, int(bool(b_is_nk)))
+    if rc != 0:
+        raise RuntimeError("gemm_ref failed with code %d" % rc)
+    return c, cabs
+
+
+def gemm_ref_samples(a, b, si, sj, b_is_nk: bool = False):
+    """c[si[t], sj[t]] and its absolute sum for each sampled output t."""
+    lib = _load_gemm()
+    M, N, K, lda, ldb = _gemm_dims(a, b, b_is_nk)
+    si = np.ascontiguousarray(si, dtype=np.int32)
+    sj = np.ascontiguousarray(sj, dtype=np.int32)
+    if si.shape != sj.shape or si.ndim != 1:
+        raise ValueError("si, sj must be 1-D and of equal length")
+    out = np.empty(si.shape[0], dtype=np.float64)
+    outabs = np.empty(si.shape[0], dtype=np.float64)
+    rc = lib.gemm_ref_f64_samples(_ptr(a), _ptr(b), _ptr(si), _ptr(sj), si.shape[0], _ptr(out), _ptr(outabs),
+                                  M, N, K, lda, ldb, int(bool(b_is_nk)))
+    if rc != 0:
+        raise RuntimeError("gemm_ref_samples failed with code %d" % rc)
+    return out, outabs

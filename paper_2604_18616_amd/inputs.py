@@ -141,3 +141,51 @@ def sample_rows(w: Workload, n: int) -> np.ndarray:
         order = np.argsort(keys, kind="stable")
         out[bh] = np.sort(order[:n])
     return out
+
+
+# ---------------------------------------------------------------------------------------
+# GEMM workloads (the paper's Section 8: square bf16 matrices with normally distributed
+# entries).  Same generator; draw order A, then B.  b_is_nk: B is stored [N,K] (a linear
+# layer's weight, C = A W^T) instead of [K,N].
+# ---------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class GemmWorkload:
+    name: str
+    M: int
+    N: int
+    K: int
+    seed: int
+    b_is_nk: bool = False
+    sigma: float = 1.0
+
+    def flops(self) -> float:
+        return 2.0 * self.M * self.N * self.K
+
+    def bytes(self) -> float:
+        """Compulsory HBM bytes: A, B read once, C written once (all bf16)."""
+        return 2.0 * (self.M * self.K + self.K * self.N + self.M * self.N)
+
+
+GEMM_WORKLOADS = {}
+for _s in (1024, 2048, 4096, 8192, 16384):
+    GEMM_WORKLOADS["G%d" % _s] = GemmWorkload("G%d" % _s, _s, _s, _s, 4000 + _s)
+    GEMM_WORKLOADS["G%dT" % _s] = GemmWorkload("G%dT" % _s, _s, _s, _s, 4000 + _s, b_is_nk=True)
+
+
+def make_ab(w: GemmWorkload):
+    """A [M,K] and B ([K,N], or [N,K] if w.b_is_nk) as uint16 arrays of bf16 bit patterns."""
+    na, nb = w.M * w.K, w.K * w.N
+    a = f32_to_bf16_bits((normal_stream(w.seed, 0, na) * w.sigma).astype(np.float32)).reshape(w.M, w.K)
+    b = f32_to_bf16_bits((normal_stream(w.seed, na, nb) * w.sigma).astype(np.float32))
+    return a, b.reshape((w.N, w.K) if w.b_is_nk else (w.K, w.N))
+
+
+def sample_outputs(w: GemmWorkload, n: int):
+    """n output coordinates (i, j) to check: tile corners and edges that exist, then seeded draws."""
+    edge_i = sorted({x for x in (0, 1, 31, 32, 127, 128, 255, 256, w.M - 2, w.M - 1) if 0 <= x < w.M})
+    edge_j = sorted({x for x in (0, 1, 31, 32, 63, 64, 255, 256, w.N - 2, w.N - 1) if 0 <= x < w.N})
+    forced = [(i, j) for i in edge_i for j in edge_j][:n]
+    r = splitmix64(np.arange(max(0, n - len(forced)), dtype=np.uint64), w.seed + 0x5EED)
+    si = np.array([p[0] for p in forced] + list((r >> np.uint64(32)) % np.uint64(w.M)), dtype=np.int32)
+    sj = np.array([p[1] for p in forced] + list((r & np.uint64(0xFFFFFFFF)) % np.uint64(w.N)), dtype=np.int32)
+    return si, sj

@@ -35,6 +35,11 @@ def load_library(build_if_missing: bool = True):
         lib.attn_fwd.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, f, p]
         lib.attn_fwd_strided.restype = i
         lib.attn_fwd_strided.argtypes = [p, p, p, p, p, i, i, i, i, i, i, p, p, p, p, i, f, p]
+        ll = ctypes.c_longlong
+        lib.gemm_bf16.restype = i
+        lib.gemm_bf16.argtypes = [p, p, p, i, i, i, ll, ll, ll, i, p]
+        lib.gemm_bf16_flops.restype = ctypes.c_double
+        lib.gemm_bf16_flops.argtypes = [i, i, i]
         lib.attn_strerror.restype = ctypes.c_char_p
         lib.attn_strerror.argtypes = [i]
         lib.attn_version.restype = i
@@ -110,3 +115,31 @@ def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
     if rc != 0:
         raise AttnError(rc, strerror(rc))
     return o, lse
+
+
+def gemm_bf16(a, b, c=None, b_is_nk=False, stream=None):
+    """C = A B for bf16 CUDA tensors a [M,K] and b [K,N] (or [N,K] if b_is_nk); rows contiguous,
+    row pitch free.  c (bf16 [M,N]) is allocated with torch if not given.  Enqueued on `stream`
+    (default: torch's current stream); no sync."""
+    import torch
+
+    if not (a.is_cuda and b.is_cuda):
+        raise ValueError("a, b must be CUDA tensors: there is no CPU path")
+    for t in (a, b):
+        if t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
+            raise ValueError("a, b must be 2-D bfloat16 tensors with contiguous rows")
+    M, K = a.shape
+    N = b.shape[0] if b_is_nk else b.shape[1]
+    if (b.shape[1] if b_is_nk else b.shape[0]) != K:
+        raise ValueError("inner dimensions differ")
+    if c is None:
+        c = torch.empty((M, N), dtype=torch.bfloat16, device=a.device)
+    if c.shape != (M, N) or c.dtype != torch.bfloat16 or c.stride(1) != 1:
+        raise ValueError("c must be bfloat16 [M,N] with contiguous rows")
+    if stream is None:
+        stream = torch.cuda.current_stream(a.device)
+    rc = load_library().gemm_bf16(a.data_ptr(), b.data_ptr(), c.data_ptr(), M, N, K,
+                                  a.stride(0), b.stride(0), c.stride(0), int(bool(b_is_nk)), stream.cuda_stream)
+    if rc != 0:
+        raise AttnError(rc, strerror(rc))
+    return c

@@ -1,0 +1,346 @@
+// bf16 GEMM for gfx950 (MI355X): C = A B with fp32 accumulation on v_mfma_f32_32x32x16_bf16
+// (the GEMM workload of the paper's Section 8; Table 2 names the ingredients: software
+// pipelining, MFMA, asynchronous copies, bank-conflict-free LDS layouts, vectorised access,
+// workgroup swizzling, guarded edge handling, explicit scheduling).
+//
+// Tiled kernel: one workgroup of 8 wavefronts owns a 256 x 256 tile of C, wavefront (wm, wn) a
+// 128 (m) x 64 (n) part of it as 4 x 2 MFMA tiles of the TRANSPOSED product (rows = n, lanes =
+// m), so that a lane ends up holding 4 consecutive n of one C row.  A and B stream through LDS
+// in 64-deep k stages, copied HBM -> LDS by global_load_lds_dwordx4 (no staging registers) into
+// XOR-swizzled tiles that the operand reads hit without bank conflicts.  B stored [K,N] is read
+// through ds_read_b64_tr_b16, which delivers the k-major MFMA operand from the n-major tile.
+//
+// Pipeline per 64-deep stage U (two LDS stages, ONE workgroup barrier per stage):
+//     operand reads of sub-step ks+1 are issued before the 8 MFMAs of sub-step ks;
+//     the copies of stage U+1 are issued one or two at a time between them;
+//     before the barrier a wavefront waits for its own reads of stage U (all four sub-steps)
+//     and for its own copies of stage U+1; after it, it reads sub-step 0 of stage U+1 while
+//     the MFMAs of sub-step 3 of stage U run.  The barrier therefore separates LDS read phases,
+//     not MFMA phases, and the matrix pipe has work across it.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_layout.h"
+#include "gemm_launch.h"
+
+namespace {
+
+using namespace gemm_layout;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+#define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
+
+template <int V> struct IntC { static constexpr int value = V; };
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (BEGIN < END) {
+        f(IntC<BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
+}
+
+// two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    f32x2 f = {lo, hi};
+    bf16x2 b = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(unsigned, b);
+}
+
+// Asynchronous 16-byte-per-lane copy HBM -> LDS: lane i's 16 bytes at (base + byte_off) land
+// at LDS address lds_addr + 16*i.  Inline asm so that the compiler's wait-count pass does not
+// tie every later LDS read to it; completion is awaited explicitly (s_waitcnt vmcnt) before the
+// barrier that publishes the stage.  M0 is written without the compiler knowing; nothing else
+// in these kernels uses M0.
+__device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_off, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
+}
+
+// ------------------------------------------------------------------------------------
+// Tiled kernel.  Requires: a, b, c 16-byte aligned; N, K, lda, ldb, ldc multiples of 8;
+// lda, ldb < 2^22.  M, N need not be multiples of the tile (source rows are clamped, stores
+// guarded); K need not be a multiple of 64 (KTAIL: pieces past K are fetched from a valid
+// address and zeroed in LDS by the copying wavefront before they are published).
+// ------------------------------------------------------------------------------------
+template <bool B_NK, bool KTAIL>
+__global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
+    __shared__ __attribute__((aligned(16))) char smem[2 * kBOffset];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+
+    const TileCoord tc = tile_coord(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n);
+    const int m0 = tc.tm * kBM, n0 = tc.tn * kBN;
+    const int M = p.M, N = p.N, K = p.K;
+    const int nK = (K + kBK - 1) / kBK;
+    const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
+    const unsigned a_rb = 2u * (unsigned)p.lda, b_rb = 2u * (unsigned)p.ldb;   // row pitches in bytes
+
+    // ---- copies: this wavefront issues instructions i = wave + 8n (n = 0..3) of each operand ----
+    unsigned a_off[4], b_off[4];   // per-lane source byte offsets relative to the stage's scalar base
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int i = wave + 8 * n;
+        const int ra = min(m0 + kt_dma_row(i, lane), M - 1) - m0;               // rows past M re-read row M-1
+        a_off[n] = (unsigned)ra * a_rb + 16u * (unsigned)kt_dma_chunk(i, lane);
+        if constexpr (B_NK) {
+            const int rb = min(n0 + kt_dma_row(i, lane), N - 1) - n0;
+            b_off[n] = (unsigned)rb * b_rb + 16u * (unsigned)kt_dma_chunk(i, lane);
+        } else {
+            const int col = min(n0 + 8 * nt_dma_chunk(i, lane), N - 8) - n0;    // columns past N re-read the last piece
+            b_off[n] = (unsigned)nt_dma_row(i, lane) * b_rb + 2u * (unsigned)col;
+        }
+    }
+    const char* const a_base = (const char*)(p.a + (long long)m0 * p.lda);
+    const char* const b_base = B_NK ? (const char*)(p.b + (long long)n0 * p.ldb) : (const char*)(p.b + n0);
+
+    // one copy instruction: j < 4 part j of A, else part j-4 of B, of stage U into LDS stage `buf`
+    auto dma = [&](int U, int buf, auto jc) __attribute__((always_inline)) {
+        constexpr int j = decltype(jc)::value;
+        constexpr int n = j & 3;
+        const int i = wave + 8 * n;
+        if constexpr (j < 4) {
+            unsigned off = a_off[n];
+            if constexpr (KTAIL)
+                if (U == nK - 1 && U * kBK + 8 * kt_dma_chunk(i, lane) >= K) off -= 16u * (unsigned)kt_dma_chunk(i, lane);
+            dma_to_lds_16B(a_base + (size_t)U * (kBK * 2), off, lds_base + buf * kStageBytes + i * 1024);
+        } else if constexpr (B_NK) {
+            unsigned off = b_off[n];
+            if constexpr (KTAIL)
+                if (U == nK - 1 && U * kBK + 8 * kt_dma_chunk(i, lane) >= K) off -= 16u * (unsigned)kt_dma_chunk(i, lane);
+            dma_to_lds_16B(b_base + (size_t)U * (kBK * 2), off, lds_base + kBOffset + buf * kStageBytes + i * 1024);
+        } else {
+            unsigned off = b_off[n];
+            if constexpr (KTAIL)
+                if (U == nK - 1 && U * kBK + nt_dma_row(i, lane) >= K) off -= (unsigned)nt_dma_row(i, lane) * b_rb;
+            dma_to_lds_16B(b_base + (size_t)U * kBK * (size_t)b_rb, off, lds_base + kBOffset + buf * kStageBytes + i * 1024);
+        }
+    };
+    // K tail: zero what this wavefront copied from past K (both operands: 0 * garbage must be 0)
+    auto zero_tail = [&](int U, int buf) __attribute__((always_inline)) {
+        if constexpr (KTAIL) {
+            if (U == nK - 1) {
+#pragma unroll
+                for (int n = 0; n < 4; ++n) {
+                    const int i = wave + 8 * n;
+                    const unsigned dst = buf * kStageBytes + i * 1024 + lane * 16;
+                    if (U * kBK + 8 * kt_dma_chunk(i, lane) >= K) *(u32x4*)(smem + dst) = u32x4{0u, 0u, 0u, 0u};
+                    const bool b_past = B_NK ? (U * kBK + 8 * kt_dma_chunk(i, lane) >= K) : (U * kBK + nt_dma_row(i, lane) >= K);
+                    if (b_past) *(u32x4*)(smem + kBOffset + dst) = u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+        }
+    };
+
+    // ---- per-lane LDS read addresses (stage 0; stage, block and sub-step offsets are immediates) ----
+    unsigned a_addr[kKS];            // second MFMA operand (lanes = m), block jm adds jm * 32 rows
+    unsigned b_addr[B_NK ? kKS : 2 * kNB];
+#pragma unroll
+    for (int ks = 0; ks < kKS; ++ks) a_addr[ks] = lds_base + kt_offset(kt_row(wm * kMB, lane), kt_chunk(ks, lane));
+    if constexpr (B_NK) {
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) b_addr[ks] = lds_base + kBOffset + kt_offset(kt_row(wn * kNB, lane), kt_chunk(ks, lane));
+    } else {
+#pragma unroll
+        for (int in = 0; in < kNB; ++in)
+#pragma unroll
+            for (int x = 0; x < 2; ++x) b_addr[2 * in + x] = lds_base + kBOffset + tr_offset(wn * kNB + in, 0, x, lane);
+    }
+
+    bf16x8 fa[2][kMB], fb[2][kNB];   // two operand sets: sub-step ks uses set ks & 1
+    auto read_frags = [&](auto bufc, auto ksc) __attribute__((always_inline)) {
+        constexpr int buf = decltype(bufc)::value, ks = decltype(ksc)::value, set = ks & 1;
+        static_for<0, kMB>([&](auto jm) __attribute__((always_inline)) {
+            fa[set][jm.value] = *LDS_PTR(bf16x8, (size_t)(a_addr[ks] + buf * kStageBytes + jm.value * 32 * 128));
+        });
+        static_for<0, kNB>([&](auto in) __attribute__((always_inline)) {
+            if constexpr (B_NK) {
+                fb[set][in.value] = *LDS_PTR(bf16x8, (size_t)(b_addr[ks] + buf * kStageBytes + in.value * 32 * 128));
+            } else {
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    LDS_PTR(s16x4, (size_t)(b_addr[2 * in.value] + buf * kStageBytes + ks * 16 * 512)));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    LDS_PTR(s16x4, (size_t)(b_addr[2 * in.value + 1] + buf * kStageBytes + ks * 16 * 512)));
+                const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                fb[set][in.value] = __builtin_bit_cast(bf16x8, v);
+            }
+        });
+    };
+
+    f32x16 acc[kNB][kMB];
+#pragma unroll
+    for (int in = 0; in < kNB; ++in)
+#pragma unroll
+        for (int jm = 0; jm < kMB; ++jm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[in][jm][r] = 0.0f;
+
+    auto mfma_set = [&](auto setc) __attribute__((always_inline)) {
+        constexpr int set = decltype(setc)::value;
+        static_for<0, kMB>([&](auto jm) __attribute__((always_inline)) {
+            static_for<0, kNB>([&](auto in) __attribute__((always_inline)) {
+                acc[in.value][jm.value] =
+                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][in.value], fa[set][jm.value], acc[in.value][jm.value], 0, 0, 0);
+            });
+        });
+    };
+    auto wait_all = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) and lgkmcnt(0): own copies landed, own LDS reads returned
+        asm volatile("" ::: "memory");
+    };
+    auto barrier = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // ---- prologue: stage 0 ----
+    static_for<0, 8>([&](auto j) __attribute__((always_inline)) { dma(0, 0, j); });
+    wait_all();
+    zero_tail(0, 0);
+    wait_all();
+    barrier();
+    read_frags(IntC<0>{}, IntC<0>{});
+
+    // one 64-deep stage held in LDS stage BUF
+    auto step = [&](auto bufc, int U) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(bufc)::value;
+        const bool more = U + 1 < nK;
+        read_frags(bufc, IntC<1>{});
+        if (more) { dma(U + 1, BUF ^ 1, IntC<0>{}); dma(U + 1, BUF ^ 1, IntC<4>{}); }
+        mfma_set(IntC<0>{});
+        read_frags(bufc, IntC<2>{});
+        if (more) { dma(U + 1, BUF ^ 1, IntC<1>{}); dma(U + 1, BUF ^ 1, IntC<5>{}); }
+        mfma_set(IntC<1>{});
+        read_frags(bufc, IntC<3>{});
+        if (more) { dma(U + 1, BUF ^ 1, IntC<2>{}); dma(U + 1, BUF ^ 1, IntC<6>{}); }
+        mfma_set(IntC<0>{});
+        if (more) { dma(U + 1, BUF ^ 1, IntC<3>{}); dma(U + 1, BUF ^ 1, IntC<7>{}); }
+        wait_all();
+        if (more) { zero_tail(U + 1, BUF ^ 1); if constexpr (KTAIL) wait_all(); }
+        barrier();
+        if (more) read_frags(IntC<BUF ^ 1>{}, IntC<0>{});
+        mfma_set(IntC<1>{});
+    };
+    for (int U = 0;;) {
+        step(IntC<0>{}, U);
+        if (++U >= nK) break;
+        step(IntC<1>{}, U);
+        if (++U >= nK) break;
+    }
+
+    // ---- epilogue: C^T fragments -> bf16 -> this wavefront's 128 x 64 staging tile -> 16-byte stores ----
+    // (every wavefront has passed the last barrier after its last LDS read and no copy is in flight)
+    char* const stage = smem + wave * (kWaveM * 128);
+    const int half = lane >> 5;
+#pragma unroll
+    for (int in = 0; in < kNB; ++in)
+#pragma unroll
+        for (int jm = 0; jm < kMB; ++jm)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int m = jm * 32 + (lane & 31);
+                const int n = in * 32 + 8 * g + 4 * half;
+                u32x2 v;
+                v[0] = pack_bf16x2(acc[in][jm][4 * g + 0], acc[in][jm][4 * g + 1]);
+                v[1] = pack_bf16x2(acc[in][jm][4 * g + 2], acc[in][jm][4 * g + 3]);
+                *(u32x2*)(stage + c_stage_offset(m, n)) = v;
+            }
+    __bf16* const ctile = p.c + (long long)(m0 + wm * kWaveM) * p.ldc + (n0 + wn * kWaveN);
+#pragma unroll
+    for (int it = 0; it < kWaveM / 8; ++it) {
+        const int row = it * 8 + (lane >> 3);
+        const int pos = lane & 7;
+        const u32x4 val = *(const u32x4*)(stage + row * 128 + pos * 16);
+        const int col = 8 * (pos ^ cswz(row));
+        if (m0 + wm * kWaveM + row < M && n0 + wn * kWaveN + col < N)
+            *(u32x4*)(ctile + (long long)row * p.ldc + col) = val;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// General kernel: any M, N, K, pitches and 2-byte-aligned pointers.  64 x 64 tile, 16-deep
+// k steps through fp32 LDS tiles with zero fill past the edges, 4 x 4 outputs per thread,
+// plain fp32 FMAs in k order.  Serves the shapes the tiled kernel's 16-byte pieces cannot.
+// ------------------------------------------------------------------------------------
+template <bool B_NK>
+__global__ __launch_bounds__(256) void gemm_bf16_general(GemmParams p) {
+    __shared__ float As[16][68];
+    __shared__ float Bs[16][68];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int tm = blockIdx.x % p.tiles_m, tn = blockIdx.x / p.tiles_m;
+    const int m0 = tm * 64, n0 = tn * 64;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < p.K; k0 += 16) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int idx = tid + 256 * t;
+            {
+                const int r = idx >> 4, kk = idx & 15;
+                const bool ok = m0 + r < p.M && k0 + kk < p.K;
+                As[kk][r] = ok ? (float)p.a[(long long)(m0 + r) * p.lda + (k0 + kk)] : 0.0f;
+            }
+            if constexpr (B_NK) {
+                const int c = idx >> 4, kk = idx & 15;
+                const bool ok = n0 + c < p.N && k0 + kk < p.K;
+                Bs[kk][c] = ok ? (float)p.b[(long long)(n0 + c) * p.ldb + (k0 + kk)] : 0.0f;
+            } else {
+                const int kk = idx >> 6, c = idx & 63;
+                const bool ok = n0 + c < p.N && k0 + kk < p.K;
+                Bs[kk][c] = ok ? (float)p.b[(long long)(k0 + kk) * p.ldb + (n0 + c)] : 0.0f;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float av[4], bv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { av[i] = As[kk][ty * 4 + i]; bv[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (m < p.M && n < p.N) p.c[(long long)m * p.ldc + n] = (__bf16)acc[i][j];
+        }
+}
+
+}  // namespace
+
+int gemm_launch(GemmParams p, int b_is_nk, bool tiled, hipStream_t stream) {
+    if (tiled) {
+        p.tiles_m = (p.M + kBM - 1) / kBM;
+        p.tiles_n = (p.N + kBN - 1) / kBN;
+        const dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(512);
+        const bool ktail = (p.K % kBK) != 0;
+#define GEMM_LAUNCH_TILED(NK, KT) hipLaunchKernelGGL((gemm_bf16_tiled<NK, KT>), grid, block, 0, stream, p)
+        if (b_is_nk) { if (ktail) GEMM_LAUNCH_TILED(true, true); else GEMM_LAUNCH_TILED(true, false); }
+        else         { if (ktail) GEMM_LAUNCH_TILED(false, true); else GEMM_LAUNCH_TILED(false, false); }
+#undef GEMM_LAUNCH_TILED
+    } else {
+        p.tiles_m = (p.M + 63) / 64;
+        p.tiles_n = (p.N + 63) / 64;
+        const dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(256);
+        if (b_is_nk) hipLaunchKernelGGL((gemm_bf16_general<true>), grid, block, 0, stream, p);
+        else         hipLaunchKernelGGL((gemm_bf16_general<false>), grid, block, 0, stream, p);
+    }
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}

@@ -1,0 +1,82 @@
+// Index maps of the tiled bf16 GEMM kernel, as constexpr functions shared by the kernel and
+// by the host-side layout test (which checks, for every lane and element, that both MFMA
+// operands of a product carry the same k, that staging is a bijection, and how LDS banks
+// are hit).  No arithmetic of the method itself lives here.
+//
+// The kernel computes C^T tiles: D'[n][m] += sum_k Bop[n][k] * Aop[k][m] with
+// v_mfma_f32_32x32x16_bf16, whose operand / result layout for lane l is (gfx950):
+//     first operand  (8 bf16): row  n = l % 32, k = 8*(l/32) + e
+//     second operand (8 bf16): col  m = l % 32, k = 8*(l/32) + e
+//     result (16 fp32)       : row  n = 8*(r/4) + 4*(l/32) + r%4,  col m = l % 32
+// so one lane ends up with 4 consecutive n of one C row m per register quad.
+#pragma once
+
+#define GEMM_HD __host__ __device__ constexpr
+
+namespace gemm_layout {
+
+constexpr int kBM = 256, kBN = 256, kBK = 64;   // workgroup tile
+constexpr int kWaveM = 128, kWaveN = 64;        // wavefront tile: 2 (m) x 4 (n) wavefronts
+constexpr int kMB = kWaveM / 32, kNB = kWaveN / 32, kKS = kBK / 16;
+constexpr int kStageBytes = kBM * kBK * 2;      // one operand, one stage: 32 KB
+constexpr int kStages = 2;
+constexpr int kBOffset = kStages * kStageBytes; // B stages follow the A stages
+
+GEMM_HD int mfma_k(int lane, int e) { return 8 * (lane >> 5) + e; }
+GEMM_HD int mfma_rc(int lane) { return lane & 31; }                       // operand row (n) / col (m)
+GEMM_HD int mfma_out_row(int lane, int r) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+// ---- tiles whose rows run along k (A; B stored [N,K]): 256 rows x 128 bytes -------------
+// 16-byte chunk c of row r sits at chunk position c ^ kswz(r): 16 consecutive rows of one
+// chunk column then cover all 64 banks.
+GEMM_HD int kswz(int row) { return (row >> 1) & 7; }
+GEMM_HD int kt_offset(int row, int chunk) { return row * 128 + ((chunk ^ kswz(row)) << 4); }
+// operand of 32-row block `blk`, reduction step ks: one 16-byte read per lane
+GEMM_HD int kt_row(int blk, int lane) { return blk * 32 + (lane & 31); }
+GEMM_HD int kt_chunk(int ks, int lane) { return 2 * ks + (lane >> 5); }
+// direct-to-LDS copy, instruction i of 32 per tile: lane's 16 bytes land at i*1024 + lane*16
+GEMM_HD int kt_dma_row(int i, int lane) { return 8 * i + (lane >> 3); }
+GEMM_HD int kt_dma_chunk(int i, int lane) { return (lane & 7) ^ kswz(kt_dma_row(i, lane)); }
+
+// ---- B stored [K,N]: tile of 64 k-rows x 512 bytes (256 n) ---------------------------------
+// read with ds_read_b64_tr_b16: in a 16-lane group, lane i receives as element j the element
+// i%4 of the 8 bytes addressed by lane 4*j + i/4.  Four consecutive k rows are XORed onto
+// four different 64-byte groups of the bank line.
+GEMM_HD int nswz(int krow) { return (krow & 3) << 2; }
+GEMM_HD int nt_offset(int krow, int chunk) { return krow * 512 + ((chunk ^ nswz(krow)) << 4); }
+// address lane `lane` supplies for read x (0,1) of n-block nb (32 columns), step ks
+GEMM_HD int tr_krow(int ks, int x, int lane) { return ks * 16 + 8 * (lane >> 5) + 4 * x + ((lane & 15) >> 2); }
+GEMM_HD int tr_ncol(int nb, int lane) { return nb * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3); }
+GEMM_HD int tr_offset(int nb, int ks, int x, int lane) {
+    return nt_offset(tr_krow(ks, x, lane), tr_ncol(nb, lane) >> 3) + ((tr_ncol(nb, lane) & 7) << 1);
+}
+// which lane's address, and which of its 4 elements, ends up as element j of lane `lane`
+GEMM_HD int tr_src_lane(int lane, int j) { return (lane & ~15) + 4 * j + ((lane & 15) >> 2); }
+GEMM_HD int tr_src_elem(int lane) { return lane & 3; }
+// copy instruction i of 32: two k rows of 512 bytes
+GEMM_HD int nt_dma_row(int i, int lane) { return 2 * i + (lane >> 5); }
+GEMM_HD int nt_dma_chunk(int i, int lane) { return (lane & 31) ^ nswz(nt_dma_row(i, lane)); }
+
+// ---- C staging (epilogue): per wavefront 128 rows (m) x 128 bytes (64 n) -------------------
+GEMM_HD int cswz(int m) { return (m >> 1) & 7; }
+GEMM_HD int c_stage_offset(int m, int n) { return m * 128 + (((n >> 3) ^ cswz(m)) << 4) + ((n & 7) << 1); }
+
+// ---- workgroup id -> C tile ------------------------------------------------------------------
+// Workgroups go to the 8 XCDs round-robin and each XCD has its own L2: every XCD gets a
+// contiguous range of the logical order, and the logical order walks the tiles in bands of 8
+// tile rows, column by column, so that the ~32 workgroups resident on one XCD cover an 8 x 4
+// patch of C and share 12 operand panels instead of 64.
+struct TileCoord { int tm, tn; };
+GEMM_HD TileCoord tile_coord(int bid, int nblocks, int tiles_m, int tiles_n) {
+    const int per_xcd = nblocks >> 3;
+    const int logical = (bid < per_xcd * 8) ? (bid & 7) * per_xcd + (bid >> 3) : bid;
+    const int GM = 8;
+    const int band = logical / (GM * tiles_n);
+    const int first = band * GM;
+    const int rows = (tiles_m - first) < GM ? (tiles_m - first) : GM;
+    const int rem = logical - band * GM * tiles_n;
+    const int tn = rem / rows;
+    return TileCoord{first + (rem - tn * rows), tn};
+}
+
+}  // namespace gemm_layout

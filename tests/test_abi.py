@@ -104,3 +104,33 @@ def test_python_binding_refuses_cpu_tensors():
     q = torch.zeros(1, 2, 8, 64, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         binding.attn_fwd(q, q, q)
+
+
+# ---------------------------------------------------------------------------------------------
+# gemm.h
+# ---------------------------------------------------------------------------------------------
+GEMM_HEADER = os.path.join(ROOT, "include", "gemm.h")
+
+
+def test_gemm_header_symbols_are_exported(lib):
+    src = re.sub(r"/\*.*?\*/", "", open(GEMM_HEADER).read(), flags=re.S)
+    names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", src)
+    assert set(names) == {"gemm_bf16", "gemm_bf16_flops"}
+    for name in names:
+        assert hasattr(lib, name), name
+    assert lib.gemm_bf16_flops(1024, 512, 256) == 2.0 * 1024 * 512 * 256
+    assert lib.gemm_bf16_flops(0, 5, 5) == 0.0
+
+
+def test_gemm_argument_errors_are_reported_without_a_gpu(lib):
+    def g(a=A16, b=A16, c=A16, M=256, N=256, K=64, lda=64, ldb=256, ldc=256, nk=0):
+        return lib.gemm_bf16(a, b, c, M, N, K, lda, ldb, ldc, nk, None)
+
+    assert g(a=None) == -1 and g(b=None) == -1 and g(c=None) == -1
+    for kw in (dict(M=0), dict(N=-1), dict(K=0)):
+        assert g(**kw) == -2, kw
+    assert g(lda=63) == -2 and g(ldb=255) == -2 and g(ldc=255) == -2
+    assert g(nk=1, ldb=63) == -2                      # B stored [N,K]: the pitch must cover K
+    assert g(lda=1 << 31) == -2
+    assert g(M=(1 << 31) - 1, N=(1 << 31) - 1, ldb=(1 << 31) - 1, ldc=(1 << 31) - 1) == -2   # too many tiles
+    assert g(a=A16 + 1) == -4 and g(c=A16 + 3) == -4  # odd addresses cannot hold bf16

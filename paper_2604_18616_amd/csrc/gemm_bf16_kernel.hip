@@ -59,9 +59,12 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
 // tie every later LDS read to it; completion is awaited explicitly (s_waitcnt vmcnt) before the
 // barrier that publishes the stage.  M0 is written without the compiler knowing; nothing else
 // in these kernels uses M0.
+// The LDS address is lds_addr + IMM with IMM an assembly-time constant: the kernels keep one
+// scalar base per wavefront instead of one scalar per destination.
+template <int IMM>
 __device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_off, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
+    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(byte_off), "s"(base), "s"(lds_addr), "n"(IMM) : "memory", "scc");
 }
 
 // ------------------------------------------------------------------------------------
@@ -72,7 +75,7 @@ __device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_o
 // ------------------------------------------------------------------------------------
 template <bool B_NK, bool KTAIL>
 __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
-    __shared__ __attribute__((aligned(16))) char smem[2 * kBOffset];
+    __shared__ __attribute__((aligned(16))) char smem[2 * kBOffset + 256];   // stages, then the warm-up loads' sink
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -86,11 +89,14 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
     const unsigned a_rb = 2u * (unsigned)p.lda, b_rb = 2u * (unsigned)p.ldb;   // row pitches in bytes
 
-    // ---- copies: this wavefront issues instructions i = wave + 8n (n = 0..3) of each operand ----
-    unsigned a_off[4], b_off[4];   // per-lane source byte offsets relative to the stage's scalar base
+    // ---- copies: wavefronts 0-3 (one per SIMD) issue them, instructions i = w + 4n (n = 0..7) of
+    // each operand; wavefronts 4-7 do not copy (4 and 5 run the L2 warm-up below) ----
+    const bool copier = wave < 4;
+    const int w4 = wave & 3;
+    unsigned a_off[8], b_off[8];   // per-lane source byte offsets relative to the stage's scalar base
 #pragma unroll
-    for (int n = 0; n < 4; ++n) {
-        const int i = wave + 8 * n;
+    for (int n = 0; n < 8; ++n) {
+        const int i = w4 + 4 * n;
         const int ra = min(m0 + kt_dma_row(i, lane), M - 1) - m0;               // rows past M re-read row M-1
         a_off[n] = (unsigned)ra * a_rb + 16u * (unsigned)kt_dma_chunk(i, lane);
         if constexpr (B_NK) {
@@ -104,35 +110,37 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
     const char* const a_base = (const char*)(p.a + (long long)m0 * p.lda);
     const char* const b_base = B_NK ? (const char*)(p.b + (long long)n0 * p.ldb) : (const char*)(p.b + n0);
 
-    // one copy instruction: j < 4 part j of A, else part j-4 of B, of stage U into LDS stage `buf`
-    auto dma = [&](int U, int buf, auto jc) __attribute__((always_inline)) {
+    // one copy instruction: j < 8 part j of A, else part j-8 of B, of stage U into LDS stage `buf`
+    const unsigned lds_copy_base = lds_base + w4 * 1024;   // instruction i = w4 + 4n lands at i * 1024
+    auto dma = [&](int U, auto bufc, auto jc) __attribute__((always_inline)) {
+        constexpr int buf = decltype(bufc)::value;
         constexpr int j = decltype(jc)::value;
-        constexpr int n = j & 3;
-        const int i = wave + 8 * n;
-        if constexpr (j < 4) {
+        constexpr int n = j & 7;
+        const int i = w4 + 4 * n;
+        if constexpr (j < 8) {
             unsigned off = a_off[n];
             if constexpr (KTAIL)
                 if (U == nK - 1 && U * kBK + 8 * kt_dma_chunk(i, lane) >= K) off -= 16u * (unsigned)kt_dma_chunk(i, lane);
-            dma_to_lds_16B(a_base + (size_t)U * (kBK * 2), off, lds_base + buf * kStageBytes + i * 1024);
+            dma_to_lds_16B<buf * kStageBytes + n * 4096>(a_base + (size_t)U * (kBK * 2), off, lds_copy_base);
         } else if constexpr (B_NK) {
             unsigned off = b_off[n];
             if constexpr (KTAIL)
                 if (U == nK - 1 && U * kBK + 8 * kt_dma_chunk(i, lane) >= K) off -= 16u * (unsigned)kt_dma_chunk(i, lane);
-            dma_to_lds_16B(b_base + (size_t)U * (kBK * 2), off, lds_base + kBOffset + buf * kStageBytes + i * 1024);
+            dma_to_lds_16B<kBOffset + buf * kStageBytes + n * 4096>(b_base + (size_t)U * (kBK * 2), off, lds_copy_base);
         } else {
             unsigned off = b_off[n];
             if constexpr (KTAIL)
                 if (U == nK - 1 && U * kBK + nt_dma_row(i, lane) >= K) off -= (unsigned)nt_dma_row(i, lane) * b_rb;
-            dma_to_lds_16B(b_base + (size_t)U * kBK * (size_t)b_rb, off, lds_base + kBOffset + buf * kStageBytes + i * 1024);
+            dma_to_lds_16B<kBOffset + buf * kStageBytes + n * 4096>(b_base + (size_t)U * kBK * (size_t)b_rb, off, lds_copy_base);
         }
     };
     // K tail: zero what this wavefront copied from past K (both operands: 0 * garbage must be 0)
     auto zero_tail = [&](int U, int buf) __attribute__((always_inline)) {
         if constexpr (KTAIL) {
-            if (U == nK - 1) {
+            if (U == nK - 1 && copier) {
 #pragma unroll
-                for (int n = 0; n < 4; ++n) {
-                    const int i = wave + 8 * n;
+                for (int n = 0; n < 8; ++n) {
+                    const int i = w4 + 4 * n;
                     const unsigned dst = buf * kStageBytes + i * 1024 + lane * 16;
                     if (U * kBK + 8 * kt_dma_chunk(i, lane) >= K) *(u32x4*)(smem + dst) = u32x4{0u, 0u, 0u, 0u};
                     const bool b_past = B_NK ? (U * kBK + 8 * kt_dma_chunk(i, lane) >= K) : (U * kBK + nt_dma_row(i, lane) >= K);
@@ -204,11 +212,53 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
         __builtin_amdgcn_sched_barrier(0);
     };
 
+    // ---- L2 warm-up --------------------------------------------------------------------------
+    // The workgroups that share an operand panel run in near lockstep, so a panel slice that is
+    // not in L2 yet is missed by all of them at once and every one waits out the HBM latency, which
+    // two LDS stages cannot cover.  kAhead stages early, one dword of each cache line of a stage
+    // is touched so that the copy issued later finds its lines in L2.  The workgroups resident on
+    // an XCD form 8 x 4 patches of tiles (tile_coord): the 4 that share an A panel each touch a
+    // quarter of its 256 lines (wavefront 4), the 8 that share a B panel an eighth (wavefront 5),
+    // which keeps the extra L2 -> L1 traffic at a fifth of the copies'.  Loads return in order, so
+    // a wavefront that also copies would meet its warm-up loads again at its next wait for the
+    // copies: wavefronts 4 and 5 issue no copies and wait for memory only once, at the end.  The
+    // loaded dwords are never used: they go to a 256-byte LDS sink, so no register waits for them.
+#ifndef GEMM_AHEAD
+#define GEMM_AHEAD 3
+#endif
+#ifndef GEMM_EARLY
+#define GEMM_EARLY 2
+#endif
+    constexpr int kEarly = GEMM_EARLY;                 // copy pairs (A, B) issued in the first sub-step, the rest in the second
+    constexpr int kAhead = GEMM_AHEAD;                 // 0 switches the warm-up off
+    const int nK_whole = KTAIL ? nK - 1 : nK;          // stages that lie wholly inside K
+    const bool warmer = kAhead > 0 && (wave == 4 || wave == 5);
+    unsigned warm_off;
+    if (wave == 4) {
+        const int r = (tc.tn & 3) * 64 + lane;
+        warm_off = (unsigned)(min(m0 + r, M - 1) - m0) * a_rb;
+    } else {
+        const int r = (tc.tm & 7) * 32 + (lane & 31);
+        if (B_NK) warm_off = (unsigned)(min(n0 + r, N - 1) - n0) * b_rb;
+        else warm_off = (unsigned)(r >> 2) * b_rb + 2u * (unsigned)(min(n0 + 64 * (r & 3), N - 2) - n0);
+    }
+    const char* const warm_base = wave == 4 ? a_base : b_base;
+    const size_t warm_step = (wave == 4 || B_NK) ? (size_t)(kBK * 2) : (size_t)kBK * (size_t)b_rb;
+    auto warm = [&](int U) __attribute__((always_inline)) {
+        const char* const src = warm_base + (size_t)U * warm_step;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                     :: "v"(warm_off), "s"(src), "s"(lds_base + 2 * kBOffset) : "memory");
+    };
+
     // ---- prologue: stage 0 ----
-    static_for<0, 8>([&](auto j) __attribute__((always_inline)) { dma(0, 0, j); });
-    wait_all();
+    if (copier) {
+        static_for<0, 16>([&](auto j) __attribute__((always_inline)) { dma(0, IntC<0>{}, j); });
+    } else if (warmer) {
+        static_for<1, kAhead>([&](auto u) __attribute__((always_inline)) { if (u.value < nK_whole) warm(u.value); });
+    }
+    if (copier) wait_all();
     zero_tail(0, 0);
-    wait_all();
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): the zeros are written
     barrier();
     read_frags(IntC<0>{}, IntC<0>{});
 
@@ -217,17 +267,29 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
         constexpr int BUF = decltype(bufc)::value;
         const bool more = U + 1 < nK;
         read_frags(bufc, IntC<1>{});
-        if (more) { dma(U + 1, BUF ^ 1, IntC<0>{}); dma(U + 1, BUF ^ 1, IntC<4>{}); }
+        if (copier) {
+            if (more) static_for<0, kEarly>([&](auto j) __attribute__((always_inline)) { dma(U + 1, IntC<BUF ^ 1>{}, j); dma(U + 1, IntC<BUF ^ 1>{}, IntC<8 + j.value>{}); });
+        } else if (warmer && U + kAhead < nK_whole) {
+            warm(U + kAhead);
+        }
         mfma_set(IntC<0>{});
         read_frags(bufc, IntC<2>{});
-        if (more) { dma(U + 1, BUF ^ 1, IntC<1>{}); dma(U + 1, BUF ^ 1, IntC<5>{}); }
+        if (copier && more) static_for<kEarly, 8>([&](auto j) __attribute__((always_inline)) { dma(U + 1, IntC<BUF ^ 1>{}, j); dma(U + 1, IntC<BUF ^ 1>{}, IntC<8 + j.value>{}); });
         mfma_set(IntC<1>{});
         read_frags(bufc, IntC<3>{});
-        if (more) { dma(U + 1, BUF ^ 1, IntC<2>{}); dma(U + 1, BUF ^ 1, IntC<6>{}); }
         mfma_set(IntC<0>{});
-        if (more) { dma(U + 1, BUF ^ 1, IntC<3>{}); dma(U + 1, BUF ^ 1, IntC<7>{}); }
-        wait_all();
-        if (more) { zero_tail(U + 1, BUF ^ 1); if constexpr (KTAIL) wait_all(); }
+        if (copier) {
+            wait_all();                             // own copies landed, own LDS reads returned
+        } else {
+            __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0) only: warm-up loads stay in flight
+            asm volatile("" ::: "memory");
+        }
+        if constexpr (KTAIL) {
+            if (U + 2 == nK) {                      // the stage just copied is the partial one
+                zero_tail(U + 1, BUF ^ 1);
+                __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0): the zeros are written
+            }
+        }
         barrier();
         if (more) read_frags(IntC<BUF ^ 1>{}, IntC<0>{});
         mfma_set(IntC<1>{});
@@ -238,6 +300,8 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
         step(IntC<1>{}, U);
         if (++U >= nK) break;
     }
+
+    wait_all();                                     // the last warm-up loads have landed
 
     // ---- epilogue: C^T fragments -> bf16 -> this wavefront's 128 x 64 staging tile -> 16-byte stores ----
     // (every wavefront has passed the last barrier after its last LDS read and no copy is in flight)

@@ -44,9 +44,9 @@ static Tile stage_kt() {
             }
         }
     CHECK(written == kStageBytes, "k-major tile not fully written: %d", written);
-    // the kernel's per-wavefront instruction split: wave w issues i = w + 8n, every i once
+    // the kernel's per-wavefront instruction split: copier wavefront w (0..3) issues i = w + 4n, every i once
     std::set<int> seen;
-    for (int w = 0; w < 8; ++w) for (int n = 0; n < 4; ++n) seen.insert(w + 8 * n);
+    for (int w = 0; w < 4; ++w) for (int n = 0; n < 8; ++n) seen.insert(w + 4 * n);
     CHECK(seen.size() == 32, "copy instructions not covered once");
     return t;
 }

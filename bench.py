@@ -1,7 +1,11 @@
 #!/usr/bin/env python3
-"""Benchmark of the MI355X attention forward (one GPU).
+"""Benchmark of the MI355X attention forward and bf16 GEMM (one GPU).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3]
+
+--workload takes an attention workload (C1..C5, P1024..P16384, N8K; default C3, the headline)
+or a GEMM workload (G1024..G16384: C = A B with B stored [K,N]; G1024T..: B stored [N,K]);
+for GEMM a step is one gemm_bf16 call and FLOPs are 2*M*N*K.
 
 A step is one attn_fwd call (the whole hot path: Q/K/V tile loads, QK^T, online
 softmax, PV, O/LSE stores) on one batch of seeded synthetic input that is already
@@ -30,9 +34,9 @@ CPU_SAMPLE_ROWS = {"C1": 0, "C2": 96, "C3": 256, "C4": 48, "C5": 32}   # rows pe
 CPU_SAMPLE_DEFAULT = 64
 
 
-def read_traffic(workload: str):
+def read_traffic(workload: str, kernel: str = "attn_fwd"):
     """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "attn_fwd_%s_hbm_traffic.txt" % workload)
+    path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.txt" % (kernel, workload))
     try:
         with open(path) as f:
             for line in f:
@@ -45,6 +49,100 @@ def read_traffic(workload: str):
 
 def prop_cus(torch, dev) -> int:
     return torch.cuda.get_device_properties(dev).multi_processor_count
+
+
+def time_steps(torch, step, stream, steps, warmup):
+    """warmup untimed steps, then `steps` timed ones: (wall ms per step, HIP-event ms per step)."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def mfma_sustained_tflops(torch, lib, dev, stream):
+    """What this GPU sustains on nothing but bf16 MFMAs (same stream, HIP events)."""
+    sink = torch.zeros(16, dtype=torch.float32, device=dev)
+    blocks, iters, sp = prop_cus(torch, dev), 20000, stream.cuda_stream
+    lib.attn_mfma_calibration(sink.data_ptr(), blocks, 2000, sp)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record(stream)
+    flops = lib.attn_mfma_calibration(sink.data_ptr(), blocks, iters, sp)
+    c1.record(stream)
+    torch.cuda.synchronize()
+    return flops / (c0.elapsed_time(c1) * 1e-3) / 1e12 if flops > 0 else None
+
+
+GEMM_CPU_SAMPLES = 1 << 17     # sampled outputs for the CPU leg of a GEMM workload
+
+
+def bench_gemm(args, torch, lib, binding, I, dev) -> int:
+    w = I.GEMM_WORKLOADS[args.workload]
+    ab, bb = I.make_ab(w)
+    to_dev = lambda x: torch.from_numpy(x.view(np.int16)).view(torch.bfloat16).to(dev)
+    a, b = to_dev(ab), to_dev(bb)
+    c = torch.full((w.M, w.N), float("nan"), dtype=torch.bfloat16, device=dev)
+    stream = torch.cuda.current_stream(dev)
+    sp = stream.cuda_stream
+    ldb = w.K if w.b_is_nk else w.N
+
+    def step():
+        rc = lib.gemm_bf16(a.data_ptr(), b.data_ptr(), c.data_ptr(), w.M, w.N, w.K, w.K, ldb, w.N, int(w.b_is_nk), sp)
+        if rc != 0:
+            raise RuntimeError(binding.strerror(rc))
+
+    ms_per_step, kernel_ms = time_steps(torch, step, stream, args.steps, args.warmup)
+    sustained = mfma_sustained_tflops(torch, lib, dev, stream)
+    flops = lib.gemm_bf16_flops(w.M, w.N, w.K)
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    achieved = flops / (kernel_ms * 1e-3) / 1e12
+
+    cpu = parity = None
+    if not args.no_cpu_baseline:
+        from oracle import gemm_ref_samples
+        n = int(min(GEMM_CPU_SAMPLES, max(4096, 2.5e9 / w.K)))
+        si, sj = I.sample_outputs(w, n)
+        c0 = time.perf_counter()
+        ref, sabs = gemm_ref_samples(ab, bb, si, sj, b_is_nk=w.b_is_nk)
+        cpu_s = time.perf_counter() - c0
+        idx = torch.from_numpy(si.astype(np.int64) * w.N + sj.astype(np.int64)).to(dev)
+        got = I.bf16_bits_to_f32(c.view(-1)[idx].view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+        err = np.abs(got - ref)
+        tol = 2.0 ** -8 * np.abs(ref) + (w.K / 16 + 4) * 2.0 ** -23 * sabs
+        parity = {"max_abs": float(err.max()), "max_err_over_tol": float((err / tol).max()), "outputs_checked": int(n),
+                  "ok": bool(np.isfinite(got).all() and (err <= tol).all())}
+        cpu = {"value": 2.0 * w.K * n / cpu_s / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+               "sample": "%d seeded output elements of %s, %.1f s" % (n, w.name, cpu_s)}
+
+    prop = torch.cuda.get_device_properties(dev)
+    out = {
+        "metric": "bf16 GEMM TFLOP/s and % of MI355X bf16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: M=%d N=%d K=%d, B stored %s, N(0,1) entries, seed %d"
+                               % (w.name, w.M, w.N, w.K, "[N,K]" if w.b_is_nk else "[K,N]", w.seed),
+                   "flops_per_step": flops, "flop_convention": "2*M*N*K"},
+        "pct_of_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": read_traffic(w.name, "gemm_bf16"),
+                     "kernel_ms": kernel_ms, "mfma_sustained_tflops": sustained,
+                     "frac_of_sustained": (achieved / sustained) if sustained else None},
+        "cpu_baseline": cpu,
+        "parity": parity,
+        "device": {"name": prop.name, "cus": prop.multi_processor_count, "clock_mhz": getattr(prop, "clock_rate", 0) / 1e3 or None},
+    }
+    print(json.dumps(out))
+    return 0 if (parity is None or parity["ok"]) else 4
 
 
 def main() -> int:
@@ -84,6 +182,8 @@ def main() -> int:
                           "copies": args.steps}))
         return 0
 
+    if args.workload in I.GEMM_WORKLOADS:
+        return bench_gemm(args, torch, lib, binding, I, dev)
     w = I.WORKLOADS[args.workload]
     qb, kb, vb = I.make_qkv(w)
     to_dev = lambda a: torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
@@ -101,35 +201,10 @@ def main() -> int:
         if rc != 0:
             raise RuntimeError(binding.strerror(rc))
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
     # timed region: K steps, wall clock bracketed by synchronize; HIP events on the launch
     # stream give the average kernel duration used for the roofline figure
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(args.steps):
-        step()
-    e1.record(stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kernel_ms = e0.elapsed_time(e1) / args.steps
-
-    # what this GPU sustains on nothing but bf16 MFMAs (same stream, same events)
-    sink = torch.zeros(16, dtype=torch.float32, device=dev)
-    cal_blocks, cal_iters = prop_cus(torch, dev), 20000
-    lib.attn_mfma_calibration(sink.data_ptr(), cal_blocks, 2000, sp)
-    torch.cuda.synchronize()
-    c0e, c1e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0e.record(stream)
-    cal_flops = lib.attn_mfma_calibration(sink.data_ptr(), cal_blocks, cal_iters, sp)
-    c1e.record(stream)
-    torch.cuda.synchronize()
-    mfma_sustained = cal_flops / (c0e.elapsed_time(c1e) * 1e-3) / 1e12 if cal_flops > 0 else None
+    ms_per_step, kernel_ms = time_steps(torch, step, stream, args.steps, args.warmup)
+    mfma_sustained = mfma_sustained_tflops(torch, lib, dev, stream)
 
     flops = lib.attn_fwd_flops(*dims, causal)
     value = flops / (ms_per_step * 1e-3) / 1e12
@@ -182,7 +257,7 @@ def main() -> int:
                      "frac_of_sustained": (achieved / mfma_sustained) if mfma_sustained else None},
         "cpu_baseline": cpu,
         "parity": parity,
-        "device": {"name": prop.name, "cus": prop.multi_processor_count},
+        "device": {"name": prop.name, "cus": prop.multi_processor_count, "clock_mhz": getattr(prop, "clock_rate", 0) / 1e3 or None},
     }
     print(json.dumps(out))
     return 0 if (parity is None or parity["ok"]) else 4

@@ -42,6 +42,16 @@ extern "C" {
 int gemm_bf16(const void *a, const void *b, void *c, int M, int N, int K,
               long long lda, long long ldb, long long ldc, int b_is_nk, void *stream);
 
+/*
+ * The same product with the workgroup tile of the matrix-core kernel chosen by the caller
+ * ("tile-size specialization" in the paper's Table 2): tile = 256 (256 x 256 tiles, one
+ * workgroup per CU), 128 (128 x 128 tiles, two per CU), or 0 (what gemm_bf16 does: 256 when
+ * that yields at least 192 tiles, else 128).  Any other value: ATTN_ERR_UNSUPPORTED.  Shapes
+ * that only the general kernel can take ignore the choice.  For tuning and for tests.
+ */
+int gemm_bf16_tile(const void *a, const void *b, void *c, int M, int N, int K,
+                   long long lda, long long ldb, long long ldc, int b_is_nk, int tile, void *stream);
+
 /* Algorithmic FLOPs of one gemm_bf16 call: 2*M*N*K (0 for invalid sizes).  Host-only helper. */
 double gemm_bf16_flops(int M, int N, int K);
 

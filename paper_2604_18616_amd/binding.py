@@ -38,6 +38,8 @@ def load_library(build_if_missing: bool = True):
         ll = ctypes.c_longlong
         lib.gemm_bf16.restype = i
         lib.gemm_bf16.argtypes = [p, p, p, i, i, i, ll, ll, ll, i, p]
+        lib.gemm_bf16_tile.restype = i
+        lib.gemm_bf16_tile.argtypes = [p, p, p, i, i, i, ll, ll, ll, i, i, p]
         lib.gemm_bf16_flops.restype = ctypes.c_double
         lib.gemm_bf16_flops.argtypes = [i, i, i]
         lib.attn_strerror.restype = ctypes.c_char_p
@@ -117,10 +119,10 @@ def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
     return o, lse
 
 
-def gemm_bf16(a, b, c=None, b_is_nk=False, stream=None):
+def gemm_bf16(a, b, c=None, b_is_nk=False, stream=None, tile=0):
     """C = A B for bf16 CUDA tensors a [M,K] and b [K,N] (or [N,K] if b_is_nk); rows contiguous,
     row pitch free.  c (bf16 [M,N]) is allocated with torch if not given.  Enqueued on `stream`
-    (default: torch's current stream); no sync."""
+    (default: torch's current stream); no sync.  tile: 0 (by size), 128 or 256 (gemm_bf16_tile)."""
     import torch
 
     if not (a.is_cuda and b.is_cuda):
@@ -138,8 +140,8 @@ def gemm_bf16(a, b, c=None, b_is_nk=False, stream=None):
         raise ValueError("c must be bfloat16 [M,N] with contiguous rows")
     if stream is None:
         stream = torch.cuda.current_stream(a.device)
-    rc = load_library().gemm_bf16(a.data_ptr(), b.data_ptr(), c.data_ptr(), M, N, K,
-                                  a.stride(0), b.stride(0), c.stride(0), int(bool(b_is_nk)), stream.cuda_stream)
+    rc = load_library().gemm_bf16_tile(a.data_ptr(), b.data_ptr(), c.data_ptr(), M, N, K,
+                                       a.stride(0), b.stride(0), c.stride(0), int(bool(b_is_nk)), int(tile), stream.cuda_stream)
     if rc != 0:
         raise AttnError(rc, strerror(rc))
     return c

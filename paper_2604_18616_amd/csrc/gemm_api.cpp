@@ -6,9 +6,10 @@
 #include "../../include/gemm.h"
 #include "gemm_launch.h"
 
-extern "C" int gemm_bf16(const void* a, const void* b, void* c, int M, int N, int K,
-                         long long lda, long long ldb, long long ldc, int b_is_nk, void* stream) {
+extern "C" int gemm_bf16_tile(const void* a, const void* b, void* c, int M, int N, int K,
+                              long long lda, long long ldb, long long ldc, int b_is_nk, int tile, void* stream) {
     if (!a || !b || !c) return ATTN_ERR_NULL_PTR;
+    if (tile != 0 && tile != 128 && tile != 256) return ATTN_ERR_UNSUPPORTED;
     if (M <= 0 || N <= 0 || K <= 0) return ATTN_ERR_BAD_SHAPE;
     if (lda < K || ldb < (b_is_nk ? K : N) || ldc < N) return ATTN_ERR_BAD_SHAPE;
     if (lda >= (1LL << 31) || ldb >= (1LL << 31) || ldc >= (1LL << 31)) return ATTN_ERR_BAD_SHAPE;
@@ -28,7 +29,12 @@ extern "C" int gemm_bf16(const void* a, const void* b, void* c, int M, int N, in
     p.M = M; p.N = N; p.K = K;
     p.lda = lda; p.ldb = ldb; p.ldc = ldc;
     p.tiles_m = 0; p.tiles_n = 0;
-    return gemm_launch(p, b_is_nk != 0, aligned && small_pitch, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+    return gemm_launch(p, b_is_nk != 0, aligned && small_pitch, tile, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int gemm_bf16(const void* a, const void* b, void* c, int M, int N, int K,
+                         long long lda, long long ldb, long long ldc, int b_is_nk, void* stream) {
+    return gemm_bf16_tile(a, b, c, M, N, K, lda, ldb, ldc, b_is_nk, 0, stream);
 }
 
 extern "C" double gemm_bf16_flops(int M, int N, int K) {

@@ -73,14 +73,18 @@ __device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_o
 // guarded); K need not be a multiple of 64 (KTAIL: pieces past K are fetched from a valid
 // address and zeroed in LDS by the copying wavefront before they are published).
 // ------------------------------------------------------------------------------------
-template <bool B_NK, bool KTAIL>
-__global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
-    __shared__ __attribute__((aligned(16))) char smem[2 * kBOffset + 256];   // stages, then the warm-up loads' sink
+template <class T, bool B_NK, bool KTAIL>
+__global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_bf16_tiled(GemmParams p) {
+    constexpr int kBM = T::BM, kBN = T::BN, kMB = T::kMB, kNB = T::kNB, kWaveM = T::kWaveM;
+    constexpr int kStageA = T::kStageA, kStageB = T::kStageB, kBOffset = T::kBOffset;
+    constexpr int kCopiers = T::kCopiers, kCopiesA = T::kCopiesA, kCopiesB = T::kCopiesB, RB = T::kNRowBytes;
+    static_assert(kCopiesA == kCopiesB, "the copy schedule pairs one A with one B instruction");
+    __shared__ __attribute__((aligned(16))) char smem[T::kLdsBytes + 256];   // stages, then the warm-up loads' sink
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave & 1, wn = wave >> 1;
+    const int wm = wave % T::WM, wn = wave / T::WM;
 
     const TileCoord tc = tile_coord(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n);
     const int m0 = tc.tm * kBM, n0 = tc.tn * kBN;
@@ -91,47 +95,47 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
 
     // ---- copies: wavefronts 0-3 (one per SIMD) issue them, instructions i = w + 4n (n = 0..7) of
     // each operand; wavefronts 4-7 do not copy (4 and 5 run the L2 warm-up below) ----
-    const bool copier = wave < 4;
-    const int w4 = wave & 3;
-    unsigned a_off[8], b_off[8];   // per-lane source byte offsets relative to the stage's scalar base
+    const bool copier = wave < kCopiers;
+    const int w4 = wave % kCopiers;
+    unsigned a_off[kCopiesA], b_off[kCopiesB];   // per-lane source byte offsets relative to the stage's scalar base
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
-        const int i = w4 + 4 * n;
+    for (int n = 0; n < kCopiesA; ++n) {
+        const int i = w4 + kCopiers * n;
         const int ra = min(m0 + kt_dma_row(i, lane), M - 1) - m0;               // rows past M re-read row M-1
         a_off[n] = (unsigned)ra * a_rb + 16u * (unsigned)kt_dma_chunk(i, lane);
         if constexpr (B_NK) {
             const int rb = min(n0 + kt_dma_row(i, lane), N - 1) - n0;
             b_off[n] = (unsigned)rb * b_rb + 16u * (unsigned)kt_dma_chunk(i, lane);
         } else {
-            const int col = min(n0 + 8 * nt_dma_chunk(i, lane), N - 8) - n0;    // columns past N re-read the last piece
-            b_off[n] = (unsigned)nt_dma_row(i, lane) * b_rb + 2u * (unsigned)col;
+            const int col = min(n0 + 8 * nt_dma_chunk<RB>(i, lane), N - 8) - n0;    // columns past N re-read the last piece
+            b_off[n] = (unsigned)nt_dma_row<RB>(i, lane) * b_rb + 2u * (unsigned)col;
         }
     }
     const char* const a_base = (const char*)(p.a + (long long)m0 * p.lda);
     const char* const b_base = B_NK ? (const char*)(p.b + (long long)n0 * p.ldb) : (const char*)(p.b + n0);
 
-    // one copy instruction: j < 8 part j of A, else part j-8 of B, of stage U into LDS stage `buf`
-    const unsigned lds_copy_base = lds_base + w4 * 1024;   // instruction i = w4 + 4n lands at i * 1024
+    // one copy instruction: j < kCopiesA part j of A, else part j-kCopiesA of B, of stage U into LDS stage `buf`
+    const unsigned lds_copy_base = lds_base + w4 * 1024;   // instruction i = w4 + kCopiers n lands at i * 1024
     auto dma = [&](int U, auto bufc, auto jc) __attribute__((always_inline)) {
         constexpr int buf = decltype(bufc)::value;
         constexpr int j = decltype(jc)::value;
-        constexpr int n = j & 7;
-        const int i = w4 + 4 * n;
-        if constexpr (j < 8) {
+        constexpr int n = j % kCopiesA;
+        const int i = w4 + kCopiers * n;
+        if constexpr (j < kCopiesA) {
             unsigned off = a_off[n];
             if constexpr (KTAIL)
                 if (U == nK - 1 && U * kBK + 8 * kt_dma_chunk(i, lane) >= K) off -= 16u * (unsigned)kt_dma_chunk(i, lane);
-            dma_to_lds_16B<buf * kStageBytes + n * 4096>(a_base + (size_t)U * (kBK * 2), off, lds_copy_base);
+            dma_to_lds_16B<buf * kStageA + n * kCopiers * 1024>(a_base + (size_t)U * (kBK * 2), off, lds_copy_base);
         } else if constexpr (B_NK) {
             unsigned off = b_off[n];
             if constexpr (KTAIL)
                 if (U == nK - 1 && U * kBK + 8 * kt_dma_chunk(i, lane) >= K) off -= 16u * (unsigned)kt_dma_chunk(i, lane);
-            dma_to_lds_16B<kBOffset + buf * kStageBytes + n * 4096>(b_base + (size_t)U * (kBK * 2), off, lds_copy_base);
+            dma_to_lds_16B<kBOffset + buf * kStageB + n * kCopiers * 1024>(b_base + (size_t)U * (kBK * 2), off, lds_copy_base);
         } else {
             unsigned off = b_off[n];
             if constexpr (KTAIL)
-                if (U == nK - 1 && U * kBK + nt_dma_row(i, lane) >= K) off -= (unsigned)nt_dma_row(i, lane) * b_rb;
-            dma_to_lds_16B<kBOffset + buf * kStageBytes + n * 4096>(b_base + (size_t)U * kBK * (size_t)b_rb, off, lds_copy_base);
+                if (U == nK - 1 && U * kBK + nt_dma_row<RB>(i, lane) >= K) off -= (unsigned)nt_dma_row<RB>(i, lane) * b_rb;
+            dma_to_lds_16B<kBOffset + buf * kStageB + n * kCopiers * 1024>(b_base + (size_t)U * kBK * (size_t)b_rb, off, lds_copy_base);
         }
     };
     // K tail: zero what this wavefront copied from past K (both operands: 0 * garbage must be 0)
@@ -139,12 +143,12 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
         if constexpr (KTAIL) {
             if (U == nK - 1 && copier) {
 #pragma unroll
-                for (int n = 0; n < 8; ++n) {
-                    const int i = w4 + 4 * n;
-                    const unsigned dst = buf * kStageBytes + i * 1024 + lane * 16;
-                    if (U * kBK + 8 * kt_dma_chunk(i, lane) >= K) *(u32x4*)(smem + dst) = u32x4{0u, 0u, 0u, 0u};
-                    const bool b_past = B_NK ? (U * kBK + 8 * kt_dma_chunk(i, lane) >= K) : (U * kBK + nt_dma_row(i, lane) >= K);
-                    if (b_past) *(u32x4*)(smem + kBOffset + dst) = u32x4{0u, 0u, 0u, 0u};
+                for (int n = 0; n < kCopiesA; ++n) {
+                    const int i = w4 + kCopiers * n;
+                    const unsigned dst = i * 1024 + lane * 16;
+                    if (U * kBK + 8 * kt_dma_chunk(i, lane) >= K) *(u32x4*)(smem + buf * kStageA + dst) = u32x4{0u, 0u, 0u, 0u};
+                    const bool b_past = B_NK ? (U * kBK + 8 * kt_dma_chunk(i, lane) >= K) : (U * kBK + nt_dma_row<RB>(i, lane) >= K);
+                    if (b_past) *(u32x4*)(smem + kBOffset + buf * kStageB + dst) = u32x4{0u, 0u, 0u, 0u};
                 }
             }
         }
@@ -162,23 +166,23 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
 #pragma unroll
         for (int in = 0; in < kNB; ++in)
 #pragma unroll
-            for (int x = 0; x < 2; ++x) b_addr[2 * in + x] = lds_base + kBOffset + tr_offset(wn * kNB + in, 0, x, lane);
+            for (int x = 0; x < 2; ++x) b_addr[2 * in + x] = lds_base + kBOffset + tr_offset<RB>(wn * kNB + in, 0, x, lane);
     }
 
     bf16x8 fa[2][kMB], fb[2][kNB];   // two operand sets: sub-step ks uses set ks & 1
     auto read_frags = [&](auto bufc, auto ksc) __attribute__((always_inline)) {
         constexpr int buf = decltype(bufc)::value, ks = decltype(ksc)::value, set = ks & 1;
         static_for<0, kMB>([&](auto jm) __attribute__((always_inline)) {
-            fa[set][jm.value] = *LDS_PTR(bf16x8, (size_t)(a_addr[ks] + buf * kStageBytes + jm.value * 32 * 128));
+            fa[set][jm.value] = *LDS_PTR(bf16x8, (size_t)(a_addr[ks] + buf * kStageA + jm.value * 32 * 128));
         });
         static_for<0, kNB>([&](auto in) __attribute__((always_inline)) {
             if constexpr (B_NK) {
-                fb[set][in.value] = *LDS_PTR(bf16x8, (size_t)(b_addr[ks] + buf * kStageBytes + in.value * 32 * 128));
+                fb[set][in.value] = *LDS_PTR(bf16x8, (size_t)(b_addr[ks] + buf * kStageB + in.value * 32 * 128));
             } else {
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    LDS_PTR(s16x4, (size_t)(b_addr[2 * in.value] + buf * kStageBytes + ks * 16 * 512)));
+                    LDS_PTR(s16x4, (size_t)(b_addr[2 * in.value] + buf * kStageB + ks * 16 * RB)));
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    LDS_PTR(s16x4, (size_t)(b_addr[2 * in.value + 1] + buf * kStageBytes + ks * 16 * 512)));
+                    LDS_PTR(s16x4, (size_t)(b_addr[2 * in.value + 1] + buf * kStageB + ks * 16 * RB)));
                 const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 fb[set][in.value] = __builtin_bit_cast(bf16x8, v);
             }
@@ -229,10 +233,10 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
 #ifndef GEMM_EARLY
 #define GEMM_EARLY 2
 #endif
-    constexpr int kEarly = GEMM_EARLY;                 // copy pairs (A, B) issued in the first sub-step, the rest in the second
+    constexpr int kEarly = GEMM_EARLY < kCopiesA ? GEMM_EARLY : kCopiesA;                 // copy pairs (A, B) issued in the first sub-step, the rest in the second
     constexpr int kAhead = GEMM_AHEAD;                 // 0 switches the warm-up off
     const int nK_whole = KTAIL ? nK - 1 : nK;          // stages that lie wholly inside K
-    const bool warmer = kAhead > 0 && (wave == 4 || wave == 5);
+    const bool warmer = kAhead > 0 && T::kWaves == 8 && (wave == 4 || wave == 5);
     unsigned warm_off;
     if (wave == 4) {
         const int r = (tc.tn & 3) * 64 + lane;
@@ -247,12 +251,12 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
     auto warm = [&](int U) __attribute__((always_inline)) {
         const char* const src = warm_base + (size_t)U * warm_step;
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-                     :: "v"(warm_off), "s"(src), "s"(lds_base + 2 * kBOffset) : "memory");
+                     :: "v"(warm_off), "s"(src), "s"(lds_base + T::kLdsBytes) : "memory");
     };
 
     // ---- prologue: stage 0 ----
     if (copier) {
-        static_for<0, 16>([&](auto j) __attribute__((always_inline)) { dma(0, IntC<0>{}, j); });
+        static_for<0, kCopiesA + kCopiesB>([&](auto j) __attribute__((always_inline)) { dma(0, IntC<0>{}, j); });
     } else if (warmer) {
         static_for<1, kAhead>([&](auto u) __attribute__((always_inline)) { if (u.value < nK_whole) warm(u.value); });
     }
@@ -268,13 +272,13 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_tiled(GemmParams p) {
         const bool more = U + 1 < nK;
         read_frags(bufc, IntC<1>{});
         if (copier) {
-            if (more) static_for<0, kEarly>([&](auto j) __attribute__((always_inline)) { dma(U + 1, IntC<BUF ^ 1>{}, j); dma(U + 1, IntC<BUF ^ 1>{}, IntC<8 + j.value>{}); });
+            if (more) static_for<0, kEarly>([&](auto j) __attribute__((always_inline)) { dma(U + 1, IntC<BUF ^ 1>{}, j); dma(U + 1, IntC<BUF ^ 1>{}, IntC<kCopiesA + j.value>{}); });
         } else if (warmer && U + kAhead < nK_whole) {
             warm(U + kAhead);
         }
         mfma_set(IntC<0>{});
         read_frags(bufc, IntC<2>{});
-        if (copier && more) static_for<kEarly, 8>([&](auto j) __attribute__((always_inline)) { dma(U + 1, IntC<BUF ^ 1>{}, j); dma(U + 1, IntC<BUF ^ 1>{}, IntC<8 + j.value>{}); });
+        if (copier && more) static_for<kEarly, kCopiesA>([&](auto j) __attribute__((always_inline)) { dma(U + 1, IntC<BUF ^ 1>{}, j); dma(U + 1, IntC<BUF ^ 1>{}, IntC<kCopiesA + j.value>{}); });
         mfma_set(IntC<1>{});
         read_frags(bufc, IntC<3>{});
         mfma_set(IntC<0>{});
@@ -389,16 +393,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_general(GemmParams p) {
 
 }  // namespace
 
-int gemm_launch(GemmParams p, int b_is_nk, bool tiled, hipStream_t stream) {
-    if (tiled) {
-        p.tiles_m = (p.M + kBM - 1) / kBM;
-        p.tiles_n = (p.N + kBN - 1) / kBN;
-        const dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(512);
-        const bool ktail = (p.K % kBK) != 0;
-#define GEMM_LAUNCH_TILED(NK, KT) hipLaunchKernelGGL((gemm_bf16_tiled<NK, KT>), grid, block, 0, stream, p)
-        if (b_is_nk) { if (ktail) GEMM_LAUNCH_TILED(true, true); else GEMM_LAUNCH_TILED(true, false); }
-        else         { if (ktail) GEMM_LAUNCH_TILED(false, true); else GEMM_LAUNCH_TILED(false, false); }
+template <class T>
+static void launch_tiled(GemmParams p, int b_is_nk, hipStream_t stream) {
+    p.tiles_m = (p.M + T::BM - 1) / T::BM;
+    p.tiles_n = (p.N + T::BN - 1) / T::BN;
+    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(T::kWaves * 64);
+    const bool ktail = (p.K % kBK) != 0;
+#define GEMM_LAUNCH_TILED(NK, KT) hipLaunchKernelGGL((gemm_bf16_tiled<T, NK, KT>), grid, block, 0, stream, p)
+    if (b_is_nk) { if (ktail) GEMM_LAUNCH_TILED(true, true); else GEMM_LAUNCH_TILED(true, false); }
+    else         { if (ktail) GEMM_LAUNCH_TILED(false, true); else GEMM_LAUNCH_TILED(false, false); }
 #undef GEMM_LAUNCH_TILED
+}
+
+// Tile-size choice: 256 x 256 tiles when they give at least ~3/4 of the chip's 256 CUs a
+// workgroup, else 128 x 128 tiles (four times the workgroups, two resident per CU).
+int gemm_launch(GemmParams p, int b_is_nk, bool tiled, int tile, hipStream_t stream) {
+    if (tiled) {
+        const long long large_tiles = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256);
+        if (tile == 256 || (tile == 0 && large_tiles >= 192)) launch_tiled<TileLarge>(p, b_is_nk, stream);
+        else launch_tiled<TileSmall>(p, b_is_nk, stream);
     } else {
         p.tiles_m = (p.M + 63) / 64;
         p.tiles_n = (p.N + 63) / 64;

@@ -13,5 +13,6 @@ struct GemmParams {
 };
 
 // Enqueue the product on `stream`; `tiled` says whether the operands satisfy the
-// alignment rules of the matrix-core kernel.  Returns 0, or -1 if the launch was refused.
-int gemm_launch(GemmParams p, int b_is_nk, bool tiled, hipStream_t stream);
+// alignment rules of the matrix-core kernel; `tile` is 0 (choose by size), 128 or 256.
+// Returns 0, or -1 if the launch was refused.
+int gemm_launch(GemmParams p, int b_is_nk, bool tiled, int tile, hipStream_t stream);

@@ -15,18 +15,36 @@
 
 namespace gemm_layout {
 
-constexpr int kBM = 256, kBN = 256, kBK = 64;   // workgroup tile
-constexpr int kWaveM = 128, kWaveN = 64;        // wavefront tile: 2 (m) x 4 (n) wavefronts
-constexpr int kMB = kWaveM / 32, kNB = kWaveN / 32, kKS = kBK / 16;
-constexpr int kStageBytes = kBM * kBK * 2;      // one operand, one stage: 32 KB
+constexpr int kBK = 64, kKS = kBK / 16;         // k depth of a stage, MFMA sub-steps per stage
 constexpr int kStages = 2;
-constexpr int kBOffset = kStages * kStageBytes; // B stages follow the A stages
+constexpr int kWaveN = 64;                      // every wavefront tile is 64 wide in n (C staging rows of 128 bytes)
+
+// Workgroup tile BM x BN computed by WM x WN wavefronts.
+//   Tile<256, 256, 2, 4>: the large-problem shape (wavefront tile 128 x 64, one workgroup per CU);
+//   Tile<128, 128, 2, 2>: four times the workgroups for problems that would leave CUs idle
+//                         (wavefront tile 64 x 64, two workgroups per CU).
+template <int BM_, int BN_, int WM_, int WN_>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+    static constexpr int kWaves = WM * WN;
+    static constexpr int kWaveM = BM / WM;
+    static constexpr int kMB = kWaveM / 32, kNB = kWaveN / 32;
+    static constexpr int kStageA = BM * kBK * 2, kStageB = BN * kBK * 2;   // bytes of one operand, one stage
+    static constexpr int kBOffset = kStages * kStageA;                      // B stages follow the A stages
+    static constexpr int kLdsBytes = kStages * (kStageA + kStageB);
+    static constexpr int kCopiers = kWaves < 4 ? kWaves : 4;                // copying wavefronts (one per SIMD)
+    static constexpr int kCopiesA = BM / 8 / kCopiers, kCopiesB = BN / 8 / kCopiers;   // 1 KB instructions per copier and stage
+    static constexpr int kNRowBytes = BN * 2;                               // row of the [k][n] tile of B stored [K,N]
+    static_assert(BN / WN == kWaveN && kWaveM % 32 == 0 && kCopiesA >= 1 && kCopiesB >= 1, "unsupported tile");
+};
+using TileLarge = Tile<256, 256, 2, 4>;
+using TileSmall = Tile<128, 128, 2, 2>;
 
 GEMM_HD int mfma_k(int lane, int e) { return 8 * (lane >> 5) + e; }
 GEMM_HD int mfma_rc(int lane) { return lane & 31; }                       // operand row (n) / col (m)
 GEMM_HD int mfma_out_row(int lane, int r) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
-// ---- tiles whose rows run along k (A; B stored [N,K]): 256 rows x 128 bytes -------------
+// ---- tiles whose rows run along k (A; B stored [N,K]): BM or BN rows x 128 bytes -----------
 // 16-byte chunk c of row r sits at chunk position c ^ kswz(r): 16 consecutive rows of one
 // chunk column then cover all 64 banks.
 GEMM_HD int kswz(int row) { return (row >> 1) & 7; }
@@ -34,30 +52,30 @@ GEMM_HD int kt_offset(int row, int chunk) { return row * 128 + ((chunk ^ kswz(ro
 // operand of 32-row block `blk`, reduction step ks: one 16-byte read per lane
 GEMM_HD int kt_row(int blk, int lane) { return blk * 32 + (lane & 31); }
 GEMM_HD int kt_chunk(int ks, int lane) { return 2 * ks + (lane >> 5); }
-// direct-to-LDS copy, instruction i of 32 per tile: lane's 16 bytes land at i*1024 + lane*16
+// direct-to-LDS copy, instruction i of rows/8 per tile: lane's 16 bytes land at i*1024 + lane*16
 GEMM_HD int kt_dma_row(int i, int lane) { return 8 * i + (lane >> 3); }
 GEMM_HD int kt_dma_chunk(int i, int lane) { return (lane & 7) ^ kswz(kt_dma_row(i, lane)); }
 
-// ---- B stored [K,N]: tile of 64 k-rows x 512 bytes (256 n) ---------------------------------
+// ---- B stored [K,N]: tile of 64 k-rows x RB bytes (RB = 2 BN: 512 or 256) ----------------------
 // read with ds_read_b64_tr_b16: in a 16-lane group, lane i receives as element j the element
 // i%4 of the 8 bytes addressed by lane 4*j + i/4.  Four consecutive k rows are XORed onto
 // four different 64-byte groups of the bank line.
 GEMM_HD int nswz(int krow) { return (krow & 3) << 2; }
-GEMM_HD int nt_offset(int krow, int chunk) { return krow * 512 + ((chunk ^ nswz(krow)) << 4); }
+template <int RB> GEMM_HD int nt_offset(int krow, int chunk) { return krow * RB + ((chunk ^ nswz(krow)) << 4); }
 // address lane `lane` supplies for read x (0,1) of n-block nb (32 columns), step ks
 GEMM_HD int tr_krow(int ks, int x, int lane) { return ks * 16 + 8 * (lane >> 5) + 4 * x + ((lane & 15) >> 2); }
 GEMM_HD int tr_ncol(int nb, int lane) { return nb * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3); }
-GEMM_HD int tr_offset(int nb, int ks, int x, int lane) {
-    return nt_offset(tr_krow(ks, x, lane), tr_ncol(nb, lane) >> 3) + ((tr_ncol(nb, lane) & 7) << 1);
+template <int RB> GEMM_HD int tr_offset(int nb, int ks, int x, int lane) {
+    return nt_offset<RB>(tr_krow(ks, x, lane), tr_ncol(nb, lane) >> 3) + ((tr_ncol(nb, lane) & 7) << 1);
 }
 // which lane's address, and which of its 4 elements, ends up as element j of lane `lane`
 GEMM_HD int tr_src_lane(int lane, int j) { return (lane & ~15) + 4 * j + ((lane & 15) >> 2); }
 GEMM_HD int tr_src_elem(int lane) { return lane & 3; }
-// copy instruction i of 32: two k rows of 512 bytes
-GEMM_HD int nt_dma_row(int i, int lane) { return 2 * i + (lane >> 5); }
-GEMM_HD int nt_dma_chunk(int i, int lane) { return (lane & 31) ^ nswz(nt_dma_row(i, lane)); }
+// copy instruction i: 1024 / RB k rows of RB bytes
+template <int RB> GEMM_HD int nt_dma_row(int i, int lane) { return (1024 / RB) * i + lane / (RB / 16); }
+template <int RB> GEMM_HD int nt_dma_chunk(int i, int lane) { return (lane % (RB / 16)) ^ nswz(nt_dma_row<RB>(i, lane)); }
 
-// ---- C staging (epilogue): per wavefront 128 rows (m) x 128 bytes (64 n) -------------------
+// ---- C staging (epilogue): per wavefront kWaveM rows (m) x 128 bytes (64 n) ------------------
 GEMM_HD int cswz(int m) { return (m >> 1) & 7; }
 GEMM_HD int c_stage_offset(int m, int n) { return m * 128 + (((n >> 3) ^ cswz(m)) << 4) + ((n & 7) << 1); }
 

@@ -25,13 +25,14 @@ using namespace gemm_layout;
 static int failures = 0;
 #define CHECK(cond, ...) do { if (!(cond)) { if (failures < 20) { printf("FAIL %s:%d: ", __FILE__, __LINE__); printf(__VA_ARGS__); printf("\n"); } ++failures; } } while (0)
 
-struct Tile { std::vector<int> row, col; Tile() : row(kStageBytes, -1), col(kStageBytes, -1) {} };
+struct Img { std::vector<int> row, col; explicit Img(int bytes) : row(bytes, -1), col(bytes, -1) {} };
 
 // k-major tile (A, or B stored [N,K]): row = m or n, col = k within the stage
-static Tile stage_kt() {
-    Tile t;
+template <class T> static Img stage_kt() {
+    constexpr int kStageBytes = T::kStageA, kBM = T::BM;
+    Img t(kStageBytes);
     int written = 0;
-    for (int i = 0; i < 32; ++i)
+    for (int i = 0; i < kBM / 8; ++i)
         for (int lane = 0; lane < 64; ++lane) {
             const int row = kt_dma_row(i, lane), chunk = kt_dma_chunk(i, lane);
             CHECK(row >= 0 && row < kBM && chunk >= 0 && chunk < 8, "bad source piece row %d chunk %d", row, chunk);
@@ -44,23 +45,27 @@ static Tile stage_kt() {
             }
         }
     CHECK(written == kStageBytes, "k-major tile not fully written: %d", written);
-    // the kernel's per-wavefront instruction split: copier wavefront w (0..3) issues i = w + 4n, every i once
+    // the kernel's per-wavefront instruction split: copier wavefront w issues i = w + kCopiers n, every i once,
+    // and its LDS destination is (w * 1024) + the assembly-time constant n * kCopiers * 1024
     std::set<int> seen;
-    for (int w = 0; w < 4; ++w) for (int n = 0; n < 8; ++n) seen.insert(w + 4 * n);
-    CHECK(seen.size() == 32, "copy instructions not covered once");
+    for (int w = 0; w < T::kCopiers; ++w) for (int n = 0; n < T::kCopiesA; ++n) seen.insert(w + T::kCopiers * n);
+    CHECK((int)seen.size() == kBM / 8 && *seen.rbegin() == kBM / 8 - 1, "copy instructions not covered once");
+    CHECK(T::kLdsBytes + 256 <= 160 * 1024 && (T::kWaves == 8 || 2 * (T::kLdsBytes + 256) <= 160 * 1024), "LDS budget");
+    CHECK(T::kWaves * T::kWaveM * 128 <= T::kLdsBytes, "C staging does not fit the stage buffers");
     return t;
 }
 
 // n-major tile (B stored [K,N]): row = k within the stage, col = n within the tile
-static Tile stage_nt() {
-    Tile t;
+template <class T> static Img stage_nt() {
+    constexpr int kStageBytes = T::kStageB, RB = T::kNRowBytes;
+    Img t(kStageBytes);
     int written = 0;
-    for (int i = 0; i < 32; ++i)
+    for (int i = 0; i < T::BN / 8; ++i)
         for (int lane = 0; lane < 64; ++lane) {
-            const int row = nt_dma_row(i, lane), chunk = nt_dma_chunk(i, lane);
-            CHECK(row >= 0 && row < kBK && chunk >= 0 && chunk < 32, "bad source piece row %d chunk %d", row, chunk);
+            const int row = nt_dma_row<RB>(i, lane), chunk = nt_dma_chunk<RB>(i, lane);
+            CHECK(row >= 0 && row < kBK && chunk >= 0 && chunk < RB / 16, "bad source piece row %d chunk %d", row, chunk);
             const int dst = i * 1024 + lane * 16;
-            CHECK(dst == nt_offset(row, chunk), "copy destination %d != layout offset %d", dst, nt_offset(row, chunk));
+            CHECK(dst == nt_offset<RB>(row, chunk), "copy destination %d != layout offset %d", dst, nt_offset<RB>(row, chunk));
             for (int b = 0; b < 16; ++b) {
                 CHECK(t.row[dst + b] < 0, "LDS byte %d written twice", dst + b);
                 t.row[dst + b] = row; t.col[dst + b] = chunk * 8 + b / 2; ++written;
@@ -70,8 +75,9 @@ static Tile stage_nt() {
     return t;
 }
 
-static int check_kt_operand(bool plant_bug) {
-    const Tile t = stage_kt();
+template <class T> static int check_kt_operand(bool plant_bug) {
+    constexpr int kStageBytes = T::kStageA, kBM = T::BM;
+    const Img t = stage_kt<T>();
     int mism = 0;
     for (int blk = 0; blk < kBM / 32; ++blk)
         for (int ks = 0; ks < kKS; ++ks)
@@ -88,7 +94,8 @@ static int check_kt_operand(bool plant_bug) {
     return mism;
 }
 
-static void check_kt_addressing() {
+template <class T> static void check_kt_addressing() {
+    constexpr int kStageBytes = T::kStageA > T::kStageB ? T::kStageA : T::kStageB, kBM = T::BM;
     // the kernel keeps one address per sub-step and adds block / stage offsets as immediates
     for (int blk = 0; blk < kBM / 32; ++blk)
         for (int ks = 0; ks < kKS; ++ks)
@@ -96,21 +103,22 @@ static void check_kt_addressing() {
                 const int base = kt_offset(kt_row(0, lane), kt_chunk(ks, lane));
                 CHECK(kt_offset(kt_row(blk, lane), kt_chunk(ks, lane)) == base + blk * 32 * 128, "block offset is not additive");
             }
-    CHECK(kStageBytes + 3 * 32 * 128 < 65536, "immediate offset of a 16-byte read exceeds 16 bits");
-    CHECK(kStageBytes + 3 * 16 * 512 < 65536, "immediate offset of a transposing read exceeds 16 bits");
+    CHECK(kStageBytes + (T::kMB - 1) * 32 * 128 < 65536, "immediate offset of a 16-byte read exceeds 16 bits");
+    CHECK(kStageBytes + 3 * 16 * T::kNRowBytes < 65536, "immediate offset of a transposing read exceeds 16 bits");
 }
 
-static void check_nt_operand() {
-    const Tile t = stage_nt();
+template <class T> static void check_nt_operand() {
+    constexpr int kStageBytes = T::kStageB, RB = T::kNRowBytes, kBN = T::BN;
+    const Img t = stage_nt<T>();
     for (int nb = 0; nb < kBN / 32; ++nb)
         for (int ks = 0; ks < kKS; ++ks)
             for (int lane = 0; lane < 64; ++lane)
                 for (int x = 0; x < 2; ++x) {
-                    CHECK(tr_offset(nb, ks, x, lane) == tr_offset(nb, 0, x, lane) + ks * 16 * 512, "sub-step offset is not additive");
+                    CHECK(tr_offset<RB>(nb, ks, x, lane) == tr_offset<RB>(nb, 0, x, lane) + ks * 16 * RB, "sub-step offset is not additive");
                     for (int j = 0; j < 4; ++j) {
                         const int s = tr_src_lane(lane, j);
-                        const int off = tr_offset(nb, ks, x, s) + 2 * tr_src_elem(lane);
-                        CHECK(off >= 0 && off + 2 <= kStageBytes && (tr_offset(nb, ks, x, s) & 7) == 0, "bad transposing-read address %d", off);
+                        const int off = tr_offset<RB>(nb, ks, x, s) + 2 * tr_src_elem(lane);
+                        CHECK(off >= 0 && off + 2 <= kStageBytes && (tr_offset<RB>(nb, ks, x, s) & 7) == 0, "bad transposing-read address %d", off);
                         const int e = 4 * x + j;
                         CHECK(t.row[off] == ks * 16 + mfma_k(lane, e), "k mismatch nb %d ks %d lane %d e %d: %d", nb, ks, lane, e, t.row[off]);
                         CHECK(t.col[off] == nb * 32 + mfma_rc(lane), "n mismatch nb %d lane %d e %d: %d", nb, lane, e, t.col[off]);
@@ -118,7 +126,8 @@ static void check_nt_operand() {
                 }
 }
 
-static void check_banks() {
+template <class T> static void check_banks() {
+    constexpr int RB = T::kNRowBytes, kBM = T::BM, kBN = T::BN;
     for (int blk = 0; blk < kBM / 32; ++blk)
         for (int ks = 0; ks < kKS; ++ks)
             for (int g = 0; g < 4; ++g) {                       // 16 lanes x 16 bytes = one 256-byte line
@@ -131,12 +140,13 @@ static void check_banks() {
             for (int x = 0; x < 2; ++x)
                 for (int h = 0; h < 2; ++h) {                   // 32 lanes x 8 bytes = one 256-byte line
                     std::set<int> slots;
-                    for (int l = 32 * h; l < 32 * h + 32; ++l) slots.insert((tr_offset(nb, ks, x, l) >> 3) & 31);
+                    for (int l = 32 * h; l < 32 * h + 32; ++l) slots.insert((tr_offset<RB>(nb, ks, x, l) >> 3) & 31);
                     CHECK(slots.size() == 32, "transposing read: bank conflict (nb %d ks %d x %d half %d)", nb, ks, x, h);
                 }
 }
 
-static void check_c_stage() {
+template <class T> static void check_c_stage() {
+    constexpr int kWaveM = T::kWaveM, kNB = T::kNB, kMB = T::kMB;
     std::vector<int> m_of(kWaveM * 128, -1), n_of(kWaveM * 128, -1);
     for (int lane = 0; lane < 64; ++lane)
         for (int in = 0; in < kNB; ++in)
@@ -188,13 +198,18 @@ static void check_tile_coord() {
     }
 }
 
+template <class T> static void check_tile_shape() {
+    CHECK(check_kt_operand<T>(false) == 0, "k-major operand read does not conform");
+    CHECK(check_kt_operand<T>(true) > 0, "planted swizzle bug was not detected");
+    check_kt_addressing<T>();
+    check_nt_operand<T>();
+    check_banks<T>();
+    check_c_stage<T>();
+}
+
 int main() {
-    CHECK(check_kt_operand(false) == 0, "k-major operand read does not conform");
-    CHECK(check_kt_operand(true) > 0, "planted swizzle bug was not detected");
-    check_kt_addressing();
-    check_nt_operand();
-    check_banks();
-    check_c_stage();
+    check_tile_shape<TileLarge>();
+    check_tile_shape<TileSmall>();
     check_tile_coord();
     if (failures) { printf("%d gemm layout check(s) FAILED\n", failures); return 1; }
     printf("gemm layout checks passed\n");

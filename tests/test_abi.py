@@ -115,7 +115,7 @@ GEMM_HEADER = os.path.join(ROOT, "include", "gemm.h")
 def test_gemm_header_symbols_are_exported(lib):
     src = re.sub(r"/\*.*?\*/", "", open(GEMM_HEADER).read(), flags=re.S)
     names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", src)
-    assert set(names) == {"gemm_bf16", "gemm_bf16_flops"}
+    assert set(names) == {"gemm_bf16", "gemm_bf16_tile", "gemm_bf16_flops"}
     for name in names:
         assert hasattr(lib, name), name
     assert lib.gemm_bf16_flops(1024, 512, 256) == 2.0 * 1024 * 512 * 256
@@ -134,3 +134,5 @@ def test_gemm_argument_errors_are_reported_without_a_gpu(lib):
     assert g(lda=1 << 31) == -2
     assert g(M=(1 << 31) - 1, N=(1 << 31) - 1, ldb=(1 << 31) - 1, ldc=(1 << 31) - 1) == -2   # too many tiles
     assert g(a=A16 + 1) == -4 and g(c=A16 + 3) == -4  # odd addresses cannot hold bf16
+    assert lib.gemm_bf16_tile(A16, A16, A16, 256, 256, 64, 64, 256, 256, 0, 64, None) == -3   # tile must be 0, 128 or 256
+    assert lib.gemm_bf16_tile(None, A16, A16, 256, 256, 64, 64, 256, 256, 0, 128, None) == -1

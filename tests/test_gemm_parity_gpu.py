@@ -30,7 +30,7 @@ def host(t):
     return I.bf16_bits_to_f32(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
 
 
-def run(a_bits, b_bits, b_is_nk, pad=(0, 0, 0), shift=0):
+def run(a_bits, b_bits, b_is_nk, pad=(0, 0, 0), shift=0, tile=0):
     """gemm_bf16 on device copies; pad = extra columns in the storage of (a, b, c) so that the
     pitches exceed the rows; shift = element offset of every pointer (alignment cases).  C starts
     as NaN, and the padding of C must stay NaN."""
@@ -49,7 +49,7 @@ def run(a_bits, b_bits, b_is_nk, pad=(0, 0, 0), shift=0):
     N = b_bits.shape[0] if b_is_nk else b_bits.shape[1]
     cbuf = torch.full((M * (N + pad[2]) + shift + 8,), float("nan"), dtype=torch.bfloat16, device="cuda")
     cfull = cbuf[shift:shift + M * (N + pad[2])].view(M, N + pad[2])
-    binding.gemm_bf16(a, b, cfull[:, :N], b_is_nk=b_is_nk)
+    binding.gemm_bf16(a, b, cfull[:, :N], b_is_nk=b_is_nk, tile=tile)
     torch.cuda.synchronize()
     if pad[2]:
         assert torch.isnan(cfull[:, N:].float()).all(), "C padding was written"
@@ -57,11 +57,11 @@ def run(a_bits, b_bits, b_is_nk, pad=(0, 0, 0), shift=0):
     return host(cfull[:, :N])
 
 
-def check_full(M, N, K, b_is_nk, seed, pad=(0, 0, 0), shift=0):
+def check_full(M, N, K, b_is_nk, seed, pad=(0, 0, 0), shift=0, tile=0):
     w = I.GemmWorkload("t", M, N, K, seed, b_is_nk=b_is_nk)
     a, b = I.make_ab(w)
-    print("gemm case M=%d N=%d K=%d nk=%d pad=%s shift=%d" % (M, N, K, b_is_nk, pad, shift), flush=True)
-    c = run(a, b, b_is_nk, pad, shift)
+    print("gemm case M=%d N=%d K=%d nk=%d pad=%s shift=%d tile=%d" % (M, N, K, b_is_nk, pad, shift, tile), flush=True)
+    c = run(a, b, b_is_nk, pad, shift, tile)
     ref, s = oracle.gemm_ref(a, b, b_is_nk=b_is_nk)
     assert np.isfinite(c).all()
     err = np.abs(c - ref)
@@ -74,15 +74,17 @@ TILED = [(256, 256, 64), (256, 256, 128), (512, 256, 192), (256, 768, 320), (300
          (1, 8, 8), (257, 8, 24), (8, 520, 136), (513, 512, 64)]
 
 
+@pytest.mark.parametrize("tile", [128, 256])
 @pytest.mark.parametrize("b_is_nk", [False, True])
 @pytest.mark.parametrize("M,N,K", TILED)
-def test_tiled_kernel_small_shapes(M, N, K, b_is_nk):
-    check_full(M, N, K, b_is_nk, seed=100 + M + N + K)
+def test_tiled_kernel_small_shapes(M, N, K, b_is_nk, tile):
+    check_full(M, N, K, b_is_nk, seed=100 + M + N + K, tile=tile)
 
 
+@pytest.mark.parametrize("tile", [128, 256])
 @pytest.mark.parametrize("b_is_nk", [False, True])
-def test_tiled_kernel_padded_pitches(b_is_nk):
-    check_full(264, 272, 200, b_is_nk, seed=7, pad=(8, 16, 24))
+def test_tiled_kernel_padded_pitches(b_is_nk, tile):
+    check_full(264, 272, 200, b_is_nk, seed=7, pad=(8, 16, 24), tile=tile)
 
 
 # general kernel: sizes, pitches or addresses the 16-byte pieces of the tiled kernel cannot take
@@ -98,18 +100,19 @@ def test_exact_small_integers():
     rng = np.random.default_rng(3)
     A = rng.integers(-3, 4, size=(256, 128)).astype(np.float32)
     B = rng.integers(-3, 4, size=(128, 256)).astype(np.float32)
-    c = run(I.f32_to_bf16_bits(A), I.f32_to_bf16_bits(B), False)
     want = A.astype(np.float64) @ B.astype(np.float64)
     assert np.abs(want).max() <= 256                   # integers up to 256 are exact in bf16
-    assert np.array_equal(c, want)
+    for tile in (128, 256):
+        assert np.array_equal(run(I.f32_to_bf16_bits(A), I.f32_to_bf16_bits(B), False, tile=tile), want)
 
 
-@pytest.mark.parametrize("name", ["G1024", "G1024T", "G2048", "G4096", "G4096T", "G8192"])
-def test_paper_sizes_on_sampled_outputs(name):
+@pytest.mark.parametrize("name,tile", [("G1024", 0), ("G1024T", 256), ("G2048", 0), ("G2048T", 0), ("G4096", 0), ("G4096T", 128),
+                                       ("G8192", 0)])
+def test_paper_sizes_on_sampled_outputs(name, tile):
     w = I.GEMM_WORKLOADS[name]
     a, b = I.make_ab(w)
-    print("gemm workload", name, flush=True)
-    c = run(a, b, w.b_is_nk)
+    print("gemm workload", name, "tile", tile, flush=True)
+    c = run(a, b, w.b_is_nk, tile=tile)
     si, sj = I.sample_outputs(w, 4096)
     ref, s = oracle.gemm_ref_samples(a, b, si, sj, b_is_nk=w.b_is_nk)
     err = np.abs(c[si, sj] - ref)

@@ -3,7 +3,8 @@
 Thin ctypes bindings of ``attn_ref.c`` (the plain definition of Section 2 of the
 paper: S = Q K^T, P = softmax(S), O = P V, plus scale, GQA, causal mask and LSE as
 the library boundary states them) and of ``gemm_ref.c`` (the bf16 matrix product of
-the paper's GEMM workload, Section 8, as three nested loops).  Only ``tests/``,
+the paper's GEMM workload, Section 8, as three nested loops) and of ``moe_ref.c`` (the
+block-quantized FP8 mixture-of-experts feed-forward of Section 8, step by step).  Only ``tests/``,
 ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import this
 package; the product package never does.  Nothing here touches a GPU or the HIP library.
 """
@@ -20,14 +21,18 @@ _SRC = os.path.join(_HERE, "attn_ref.c")
 _LIB = os.path.join(_HERE, "liboracle_attn.so")
 _GEMM_SRC = os.path.join(_HERE, "gemm_ref.c")
 _GEMM_LIB = os.path.join(_HERE, "liboracle_gemm.so")
+_MOE_SRC = os.path.join(_HERE, "moe_ref.c")
+_MOE_LIB = os.path.join(_HERE, "liboracle_moe.so")
 _lib = None
 _gemm_lib = None
+_moe_lib = None
 
 
 def _compile(src: str, lib: str, force: bool) -> str:
     if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
         tmp = lib + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+        # -ffp-contract=off: the fp32 steps of the quantization recipes must not be fused
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra",
                                "-o", tmp, src, "-lm"])
         os.replace(tmp, lib)
     return lib
@@ -36,6 +41,7 @@ def _compile(src: str, lib: str, force: bool) -> str:
 def build(force: bool = False) -> str:
     """Compile the C references with gcc (plain -O2, no fast-math); returns the attention .so path."""
     _compile(_GEMM_SRC, _GEMM_LIB, force)
+    _compile(_MOE_SRC, _MOE_LIB, force)
     return _compile(_SRC, _LIB, force)
 
 
@@ -176,3 +182,67 @@ def gemm_ref_samples(a, b, si, sj, b_is_nk: bool = False):
     if rc != 0:
         raise RuntimeError("gemm_ref_samples failed with code %d" % rc)
     return out, outabs
+
+
+def _load_moe():
+    global _moe_lib
+    if _moe_lib is None:
+        lib = ctypes.CDLL(_compile(_MOE_SRC, _MOE_LIB, False))
+        i, p = ctypes.c_int, ctypes.c_void_p
+        lib.moe_ref_f64.restype = i
+        lib.moe_ref_f64.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, p, i]
+        lib.moe_ref_e4m3_decode.restype = ctypes.c_double
+        lib.moe_ref_e4m3_decode.argtypes = [ctypes.c_uint8]
+        lib.moe_ref_e4m3_encode.restype = ctypes.c_uint8
+        lib.moe_ref_e4m3_encode.argtypes = [ctypes.c_float]
+        lib.moe_ref_quant_group.restype = None
+        lib.moe_ref_quant_group.argtypes = [p, p, p]
+        _moe_lib = lib
+    return _moe_lib
+
+
+def e4m3_decode(code: int) -> float:
+    return float(_load_moe().moe_ref_e4m3_decode(int(code)))
+
+
+def e4m3_encode(value: float) -> int:
+    return int(_load_moe().moe_ref_e4m3_encode(float(np.float32(value))))
+
+
+def quant_group(v):
+    """e4m3 codes [128] and the fp32 scale of one group of 128 fp32 values."""
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    if v.shape != (128,):
+        raise ValueError("a group has 128 values")
+    code = np.empty(128, dtype=np.uint8)
+    scale = np.empty(1, dtype=np.float32)
+    _load_moe().moe_ref_quant_group(_ptr(v), _ptr(code), _ptr(scale))
+    return code, float(scale[0])
+
+
+def moe_ref(x, ids, wts, w13, s13, w2, s2, rows=None):
+    """Reference MoE feed-forward output (fp64) for all tokens or the listed ones: [R, H].
+
+    x [T,H] uint16 (bf16 bits); ids [T,KTOP] int32 (local expert or negative); wts [T,KTOP] fp32;
+    w13 [E,2I,H] / w2 [E,H,I] uint8 e4m3 codes; s13 [E,2I/128,H/128] / s2 [E,H/128,I/128] fp32.
+    """
+    lib = _load_moe()
+    T, H = x.shape
+    E, I2, _ = w13.shape
+    I, K = I2 // 2, ids.shape[1]
+    if w13.shape != (E, 2 * I, H) or w2.shape != (E, H, I) or ids.shape != (T, K) or wts.shape != (T, K) \
+            or s13.shape != (E, 2 * I // 128, H // 128) or s2.shape != (E, H // 128, I // 128):
+        raise ValueError("inconsistent MoE shapes")
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    wts = np.ascontiguousarray(wts, dtype=np.float32)
+    w13, w2 = np.ascontiguousarray(w13, dtype=np.uint8), np.ascontiguousarray(w2, dtype=np.uint8)
+    s13, s2 = np.ascontiguousarray(s13, dtype=np.float32), np.ascontiguousarray(s2, dtype=np.float32)
+    rows_a = None if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
+    R = T if rows_a is None else rows_a.shape[0]
+    y = np.empty((R, H), dtype=np.float64)
+    rc = lib.moe_ref_f64(_ptr(x), _ptr(ids), _ptr(wts), _ptr(w13), _ptr(s13), _ptr(w2), _ptr(s2), _ptr(y),
+                         T, H, I, E, K, _ptr(rows_a) if rows_a is not None else None, R)
+    if rc != 0:
+        raise RuntimeError("moe_ref failed with code %d" % rc)
+    return y

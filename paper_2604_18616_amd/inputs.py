@@ -189,3 +189,122 @@ def sample_outputs(w: GemmWorkload, n: int):
     si = np.array([p[0] for p in forced] + list((r >> np.uint64(32)) % np.uint64(w.M)), dtype=np.int32)
     sj = np.array([p[1] for p in forced] + list((r & np.uint64(0xFFFFFFFF)) % np.uint64(w.N)), dtype=np.int32)
     return si, sj
+
+
+# ---------------------------------------------------------------------------------------
+# Fused-MoE workloads (the paper's Section 8: block-quantized FP8 feed-forward experts, model
+# dimension 7168, intermediate dimension 2048, top-4 routing, 32 experts per GPU under 8-way
+# expert parallelism).  The paper gives the shape only; the rest is this build's recipe:
+#   x        [T,H] bf16, iid N(0,1);
+#   routing  each token draws 4 distinct experts out of E*EP global ones; the ids handed to the
+#            library are local (0..E-1) or -1 for experts that live on another GPU; the 4
+#            weights are positive and sum to 1;
+#   weights  e4m3 codes whose values are round(64 * N(0,1)) in e4m3 (16-bit inverse-CDF draws),
+#            block scales (one per 128 x 128 block) = (1 + u/4) / (64 sqrt(fan_in)), u in [0,1).
+# The encoder below serves input generation only (nearest value, table search).
+# ---------------------------------------------------------------------------------------
+def e4m3_values() -> np.ndarray:
+    """The 256 e4m3 code values as fp64 (NaN for the two NaN codes)."""
+    c = np.arange(256)
+    e, m = (c >> 3) & 15, (c & 7).astype(np.float64)
+    v = np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7))
+    v = np.where((e == 15) & ((c & 7) == 7), np.nan, v)
+    return np.where(c >= 128, -v, v)
+
+
+def nearest_e4m3(v: np.ndarray) -> np.ndarray:
+    """Nearest e4m3 code of each value (|v| clamped to 448); for building inputs only."""
+    pos = e4m3_values()[:127]                      # 0 .. 448, ascending
+    a = np.minimum(np.abs(v), 448.0)
+    hi = np.clip(np.searchsorted(pos, a), 1, 126)
+    lo = hi - 1
+    code = np.where(a - pos[lo] <= pos[hi] - a, lo, hi).astype(np.uint8)
+    return np.where(v < 0, code | 0x80, code).astype(np.uint8)
+
+
+_CODE_TABLE = None
+
+
+def _normal_code_table() -> np.ndarray:
+    global _CODE_TABLE
+    if _CODE_TABLE is None:
+        from statistics import NormalDist
+        nd = NormalDist()
+        z = np.array([nd.inv_cdf((u + 0.5) / 65536.0) for u in range(65536)])
+        _CODE_TABLE = nearest_e4m3(64.0 * z)
+    return _CODE_TABLE
+
+
+def random_e4m3(seed: int, n: int) -> np.ndarray:
+    """n e4m3 codes with values ~ 64 * N(0,1), four per splitmix64 draw."""
+    table = _normal_code_table()
+    out = np.empty((n + 3) // 4 * 4, dtype=np.uint8)
+    chunk = 1 << 22
+    for lo in range(0, out.size // 4, chunk):
+        hi = min(out.size // 4, lo + chunk)
+        r = splitmix64(np.arange(lo, hi, dtype=np.uint64), seed)
+        for q in range(4):
+            out[4 * lo + q:4 * hi:4] = table[((r >> np.uint64(16 * q)) & np.uint64(0xFFFF)).astype(np.int64)]
+    return out[:n]
+
+
+@dataclass(frozen=True)
+class MoeWorkload:
+    name: str
+    T: int
+    seed: int
+    H: int = 7168
+    I: int = 2048
+    E: int = 32          # experts on this GPU
+    KTOP: int = 4
+    EP: int = 8          # expert-parallel ranks: E * EP experts in total
+
+    def local_slots(self, ids: np.ndarray) -> int:
+        return int((ids >= 0).sum())
+
+    def flops(self, ids: np.ndarray) -> float:
+        """Algorithmic FLOPs: 2 * (2I*H + H*I) per routed (token, local expert) pair."""
+        return 6.0 * self.H * self.I * self.local_slots(ids)
+
+    def bytes(self, ids: np.ndarray) -> float:
+        """Compulsory HBM bytes: x read and y written (bf16), the weights of the experts that
+        receive a token read once (1 byte each), routing tables."""
+        used = len(set(ids[ids >= 0].tolist()))
+        return 4.0 * self.T * self.H + 3.0 * self.H * self.I * used + 8.0 * self.T * self.KTOP
+
+
+MOE_WORKLOADS = {("M%d" % _t): MoeWorkload("M%d" % _t, _t, 5000 + _t) for _t in (1024, 2048, 4096, 8192, 16384)}
+
+
+def make_moe(w: MoeWorkload):
+    """dict with x [T,H] (bf16 bits), ids [T,KTOP] int32, wts [T,KTOP] fp32, w13 [E,2I,H] and
+    w2 [E,H,I] (e4m3 codes), s13 [E,2I/128,H/128] and s2 [E,H/128,I/128] (fp32)."""
+    T, H, I, E, K = w.T, w.H, w.I, w.E, w.KTOP
+    x = f32_to_bf16_bits(normal_stream(w.seed, 0, T * H).astype(np.float32)).reshape(T, H)
+    total = E * w.EP
+    keys = splitmix64(np.arange(T * total, dtype=np.uint64), w.seed + 1).reshape(T, total)
+    glob = np.argsort(keys, axis=1, kind="stable")[:, :K]                  # K distinct experts per token
+    ids = np.where(glob < E, glob, -1).astype(np.int32)                    # rank 0 owns experts 0..E-1
+    u = (splitmix64(np.arange(T * K, dtype=np.uint64), w.seed + 2) >> np.uint64(40)).astype(np.float64) / 2.0 ** 24 + 0.25
+    wts = (u.reshape(T, K) / u.reshape(T, K).sum(axis=1, keepdims=True)).astype(np.float32)
+    w13 = random_e4m3(w.seed + 3, E * 2 * I * H).reshape(E, 2 * I, H)
+    w2 = random_e4m3(w.seed + 4, E * H * I).reshape(E, H, I)
+
+    def scales(seed, shape, fan_in):
+        n = int(np.prod(shape))
+        uu = (splitmix64(np.arange(n, dtype=np.uint64), seed) >> np.uint64(40)).astype(np.float64) / 2.0 ** 24
+        return ((1.0 + uu / 4.0) / (64.0 * np.sqrt(fan_in))).astype(np.float32).reshape(shape)
+
+    s13 = scales(w.seed + 5, (E, 2 * I // 128, H // 128), H)
+    s2 = scales(w.seed + 6, (E, H // 128, I // 128), I)
+    return dict(x=x, ids=ids, wts=wts, w13=w13, s13=s13, w2=w2, s2=s2)
+
+
+def sample_tokens(w: MoeWorkload, ids: np.ndarray, n: int) -> np.ndarray:
+    """n tokens to check: the first and last token, then seeded draws weighted toward tokens that
+    have at least one local expert (the others must come out as exact zeros and cost nothing)."""
+    order = np.argsort(splitmix64(np.arange(w.T, dtype=np.uint64), w.seed + 7), kind="stable")
+    local = order[(ids[order] >= 0).any(axis=1)]
+    remote = order[~(ids[order] >= 0).any(axis=1)]
+    pick = [0, w.T - 1] + local[:max(0, n - 2 - min(4, len(remote)))].tolist() + remote[:4].tolist()
+    return np.array(sorted(set(pick))[:n], dtype=np.int32)

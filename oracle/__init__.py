@@ -195,6 +195,10 @@ def _load_moe():
         lib.moe_ref_e4m3_decode.argtypes = [ctypes.c_uint8]
         lib.moe_ref_e4m3_encode.restype = ctypes.c_uint8
         lib.moe_ref_e4m3_encode.argtypes = [ctypes.c_float]
+        lib.moe_ref_intermediate_f64.restype = i
+        lib.moe_ref_intermediate_f64.argtypes = [p, p, p, p, i, i, i, i, i, i]
+        lib.moe_ref_down_f64.restype = i
+        lib.moe_ref_down_f64.argtypes = [p, p, p, p, p, i, i, i, i]
         lib.moe_ref_quant_group.restype = None
         lib.moe_ref_quant_group.argtypes = [p, p, p]
         _moe_lib = lib
@@ -246,3 +250,33 @@ def moe_ref(x, ids, wts, w13, s13, w2, s2, rows=None):
     if rc != 0:
         raise RuntimeError("moe_ref failed with code %d" % rc)
     return y
+
+
+def moe_intermediate(x, w13, s13, t: int, e: int):
+    """Steps 1-2 of the MoE reference for token t on local expert e: the gated intermediate a [I] in
+    fp64, before it is rounded to fp32 and requantized."""
+    T, H = x.shape
+    E, I2, _ = w13.shape
+    a = np.empty(I2 // 2, dtype=np.float64)
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    w13, s13 = np.ascontiguousarray(w13, dtype=np.uint8), np.ascontiguousarray(s13, dtype=np.float32)
+    rc = _load_moe().moe_ref_intermediate_f64(_ptr(x), _ptr(w13), _ptr(s13), _ptr(a), T, H, I2 // 2, E, int(t), int(e))
+    if rc != 0:
+        raise RuntimeError("moe_intermediate failed with code %d" % rc)
+    return a
+
+
+def moe_down(aq, a_scales, w2, s2, e: int):
+    """Step 4 alone: the down-projection row o [H] (fp64) of given intermediate codes aq [I] (uint8)
+    and group scales [I/128] (fp32) on local expert e."""
+    E, H, I = w2.shape
+    aq = np.ascontiguousarray(aq, dtype=np.uint8)
+    a_scales = np.ascontiguousarray(a_scales, dtype=np.float32)
+    if aq.shape != (I,) or a_scales.shape != (I // 128,):
+        raise ValueError("aq [I], scales [I/128]")
+    w2, s2 = np.ascontiguousarray(w2, dtype=np.uint8), np.ascontiguousarray(s2, dtype=np.float32)
+    o = np.empty(H, dtype=np.float64)
+    rc = _load_moe().moe_ref_down_f64(_ptr(aq), _ptr(a_scales), _ptr(w2), _ptr(s2), _ptr(o), H, I, E, int(e))
+    if rc != 0:
+        raise RuntimeError("moe_down failed with code %d" % rc)
+    return o

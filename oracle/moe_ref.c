@@ -100,6 +100,72 @@ void moe_ref_quant_group(const float *v, uint8_t *code, float *scale)
     *scale = s;
 }
 
+/* steps 1-2 for one (token, local expert): a_j in fp64, before it is rounded to fp32 for step 3 */
+static void slot_intermediate(const uint16_t *xrow, const uint8_t *w13e, const float *s13e, const double *dec,
+                              int H, int I, uint8_t *xq, float *xs, float *xf, double *a)
+{
+    const int HB = H / 128;
+    for (int h = 0; h < H; ++h) xf[h] = bf16_bits_to_f32(xrow[h]);
+    for (int b = 0; b < HB; ++b) moe_ref_quant_group(xf + 128 * b, xq + 128 * b, xs + b);
+    for (int j = 0; j < I; ++j) {
+        double gu[2];
+        for (int part = 0; part < 2; ++part) {
+            const int row = part * I + j;
+            double acc = 0.0;
+            for (int b = 0; b < HB; ++b) {
+                double blk = 0.0;
+                for (int h = 128 * b; h < 128 * b + 128; ++h) blk += dec[xq[h]] * dec[w13e[(size_t)row * (size_t)H + (size_t)h]];
+                acc += blk * (double)xs[b] * (double)s13e[(size_t)(row / 128) * (size_t)HB + (size_t)b];
+            }
+            gu[part] = acc;
+        }
+        a[j] = gu[0] / (1.0 + exp(-gu[0])) * gu[1];
+    }
+}
+
+/* step 4 for one row of intermediate codes and scales */
+static void slot_down(const uint8_t *aq, const float *as, const uint8_t *w2e, const float *s2e, const double *dec,
+                      int H, int I, double *o)
+{
+    const int IB = I / 128;
+    for (int c = 0; c < H; ++c) {
+        double acc = 0.0;
+        for (int b = 0; b < IB; ++b) {
+            double blk = 0.0;
+            for (int j = 128 * b; j < 128 * b + 128; ++j) blk += dec[aq[j]] * dec[w2e[(size_t)c * (size_t)I + (size_t)j]];
+            acc += blk * (double)as[b] * (double)s2e[(size_t)(c / 128) * (size_t)IB + (size_t)b];
+        }
+        o[c] = acc;
+    }
+}
+
+/* The intermediate a [I] (fp64, unrounded) of token t on local expert e.  Returns 0, or nonzero on bad arguments. */
+int moe_ref_intermediate_f64(const uint16_t *x, const uint8_t *w13, const float *s13, double *a,
+                             int T, int H, int I, int E, int t, int e)
+{
+    if (!x || !w13 || !s13 || !a || T <= 0 || H <= 0 || I <= 0 || H % 128 || I % 128 || t < 0 || t >= T || e < 0 || e >= E) return 1;
+    double dec[256];
+    for (int c = 0; c < 256; ++c) dec[c] = moe_ref_e4m3_decode((uint8_t)c);
+    uint8_t *xq = malloc((size_t)H);
+    float *xs = malloc(sizeof(float) * (size_t)(H / 128)), *xf = malloc(sizeof(float) * (size_t)H);
+    if (!xq || !xs || !xf) return 2;
+    slot_intermediate(x + (size_t)t * (size_t)H, w13 + (size_t)e * 2 * (size_t)I * (size_t)H,
+                      s13 + (size_t)e * 2 * (size_t)(I / 128) * (size_t)(H / 128), dec, H, I, xq, xs, xf, a);
+    free(xq); free(xs); free(xf);
+    return 0;
+}
+
+/* Step 4 alone: o [H] (fp64) from given intermediate codes aq [I] and scales as [I/128] on expert e. */
+int moe_ref_down_f64(const uint8_t *aq, const float *as, const uint8_t *w2, const float *s2, double *o,
+                     int H, int I, int E, int e)
+{
+    if (!aq || !as || !w2 || !s2 || !o || H <= 0 || I <= 0 || H % 128 || I % 128 || e < 0 || e >= E) return 1;
+    double dec[256];
+    for (int c = 0; c < 256; ++c) dec[c] = moe_ref_e4m3_decode((uint8_t)c);
+    slot_down(aq, as, w2 + (size_t)e * (size_t)H * (size_t)I, s2 + (size_t)e * (size_t)(H / 128) * (size_t)(I / 128), dec, H, I, o);
+    return 0;
+}
+
 int moe_ref_f64(const uint16_t *x, const int32_t *ids, const float *wts,
                 const uint8_t *w13, const float *s13, const uint8_t *w2, const float *s2,
                 double *y, int T, int H, int I, int E, int KTOP, const int *rows, int nrows)
@@ -112,48 +178,25 @@ int moe_ref_f64(const uint16_t *x, const int32_t *ids, const float *wts,
     uint8_t *xq = malloc((size_t)H), *aq = malloc((size_t)I);
     float *xs = malloc(sizeof(float) * (size_t)HB), *as = malloc(sizeof(float) * (size_t)IB);
     float *xf = malloc(sizeof(float) * (size_t)H), *af = malloc(sizeof(float) * (size_t)I);
-    if (!xq || !aq || !xs || !as || !xf || !af) return 2;
+    double *ad = malloc(sizeof(double) * (size_t)I), *od = malloc(sizeof(double) * (size_t)H);
+    if (!xq || !aq || !xs || !as || !xf || !af || !ad || !od) return 2;
     for (int r = 0; r < R; ++r) {
         const int t = rows ? rows[r] : r;
         if (t < 0 || t >= T) return 1;
         double *yr = y + (size_t)r * (size_t)H;
         for (int c = 0; c < H; ++c) yr[c] = 0.0;
-        for (int h = 0; h < H; ++h) xf[h] = bf16_bits_to_f32(x[(size_t)t * (size_t)H + (size_t)h]);
-        for (int b = 0; b < HB; ++b) moe_ref_quant_group(xf + 128 * b, xq + 128 * b, xs + b);
         for (int k = 0; k < KTOP; ++k) {
             const int e = ids[(size_t)t * (size_t)KTOP + (size_t)k];
             if (e < 0 || e >= E) continue;
-            const uint8_t *w13e = w13 + (size_t)e * 2 * (size_t)I * (size_t)H;
-            const float *s13e = s13 + (size_t)e * 2 * (size_t)IB * (size_t)HB;
-            for (int j = 0; j < I; ++j) {
-                double gu[2];
-                for (int part = 0; part < 2; ++part) {
-                    const int row = part * I + j;
-                    double acc = 0.0;
-                    for (int b = 0; b < HB; ++b) {
-                        double blk = 0.0;
-                        for (int h = 128 * b; h < 128 * b + 128; ++h) blk += dec[xq[h]] * dec[w13e[(size_t)row * (size_t)H + (size_t)h]];
-                        acc += blk * (double)xs[b] * (double)s13e[(size_t)(row / 128) * (size_t)HB + (size_t)b];
-                    }
-                    gu[part] = acc;
-                }
-                af[j] = (float)(gu[0] / (1.0 + exp(-gu[0])) * gu[1]);
-            }
+            slot_intermediate(x + (size_t)t * (size_t)H, w13 + (size_t)e * 2 * (size_t)I * (size_t)H,
+                              s13 + (size_t)e * 2 * (size_t)IB * (size_t)HB, dec, H, I, xq, xs, xf, ad);
+            for (int j = 0; j < I; ++j) af[j] = (float)ad[j];
             for (int b = 0; b < IB; ++b) moe_ref_quant_group(af + 128 * b, aq + 128 * b, as + b);
-            const uint8_t *w2e = w2 + (size_t)e * (size_t)H * (size_t)I;
-            const float *s2e = s2 + (size_t)e * (size_t)HB * (size_t)IB;
+            slot_down(aq, as, w2 + (size_t)e * (size_t)H * (size_t)I, s2 + (size_t)e * (size_t)HB * (size_t)IB, dec, H, I, od);
             const double wk = (double)wts[(size_t)t * (size_t)KTOP + (size_t)k];
-            for (int c = 0; c < H; ++c) {
-                double acc = 0.0;
-                for (int b = 0; b < IB; ++b) {
-                    double blk = 0.0;
-                    for (int j = 128 * b; j < 128 * b + 128; ++j) blk += dec[aq[j]] * dec[w2e[(size_t)c * (size_t)I + (size_t)j]];
-                    acc += blk * (double)as[b] * (double)s2e[(size_t)(c / 128) * (size_t)IB + (size_t)b];
-                }
-                yr[c] += wk * acc;
-            }
+            for (int c = 0; c < H; ++c) yr[c] += wk * od[c];
         }
     }
-    free(xq); free(aq); free(xs); free(as); free(xf); free(af);
+    free(xq); free(aq); free(xs); free(as); free(xf); free(af); free(ad); free(od);
     return 0;
 }

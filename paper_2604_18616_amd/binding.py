@@ -42,6 +42,14 @@ def load_library(build_if_missing: bool = True):
         lib.gemm_bf16_tile.argtypes = [p, p, p, i, i, i, ll, ll, ll, i, i, p]
         lib.gemm_bf16_flops.restype = ctypes.c_double
         lib.gemm_bf16_flops.argtypes = [i, i, i]
+        lib.moe_ffn_fp8_workspace_bytes.restype = ctypes.c_size_t
+        lib.moe_ffn_fp8_workspace_bytes.argtypes = [i, i, i, i, i]
+        lib.moe_ffn_fp8_workspace_offset.restype = ctypes.c_longlong
+        lib.moe_ffn_fp8_workspace_offset.argtypes = [i, i, i, i, i, i]
+        lib.moe_ffn_fp8.restype = i
+        lib.moe_ffn_fp8.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, p, ctypes.c_size_t, p]
+        lib.moe_ffn_fp8_flops_per_pair.restype = ctypes.c_double
+        lib.moe_ffn_fp8_flops_per_pair.argtypes = [i, i]
         lib.attn_strerror.restype = ctypes.c_char_p
         lib.attn_strerror.argtypes = [i]
         lib.attn_version.restype = i
@@ -145,3 +153,46 @@ def gemm_bf16(a, b, c=None, b_is_nk=False, stream=None, tile=0):
     if rc != 0:
         raise AttnError(rc, strerror(rc))
     return c
+
+
+def moe_workspace_bytes(T, H, I, E, KTOP) -> int:
+    return int(load_library().moe_ffn_fp8_workspace_bytes(T, H, I, E, KTOP))
+
+
+def moe_workspace_offset(T, H, I, E, KTOP, part: int) -> int:
+    return int(load_library().moe_ffn_fp8_workspace_offset(T, H, I, E, KTOP, part))
+
+
+def moe_ffn_fp8(x, ids, wts, w13, s13, w2, s2, y=None, workspace=None, stream=None):
+    """Block-quantized FP8 MoE feed-forward of CUDA tensors: x bf16 [T,H]; ids int32 [T,KTOP] (local
+    expert or negative); wts fp32 [T,KTOP]; w13 uint8 [E,2I,H] and w2 uint8 [E,H,I] (e4m3 codes);
+    s13 fp32 [E,2I/128,H/128]; s2 fp32 [E,H/128,I/128].  y (bf16 [T,H]) and the workspace (uint8, at
+    least moe_workspace_bytes(...)) are allocated with torch if not given.  Enqueued on `stream`
+    (default: torch's current stream); no sync."""
+    import torch
+
+    for t in (x, ids, wts, w13, s13, w2, s2):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("all MoE tensors must be contiguous CUDA tensors: there is no CPU path")
+    T, H = x.shape
+    E, I2, _ = w13.shape
+    I, K = I2 // 2, ids.shape[1]
+    if (x.dtype != torch.bfloat16 or ids.dtype != torch.int32 or wts.dtype != torch.float32 or w13.dtype != torch.uint8
+            or w2.dtype != torch.uint8 or s13.dtype != torch.float32 or s2.dtype != torch.float32):
+        raise ValueError("dtypes: x bf16, ids int32, wts/s13/s2 fp32, w13/w2 uint8")
+    if (w13.shape != (E, 2 * I, H) or w2.shape != (E, H, I) or ids.shape != (T, K) or wts.shape != (T, K)
+            or s13.shape != (E, 2 * I // 128, H // 128) or s2.shape != (E, H // 128, I // 128)):
+        raise ValueError("inconsistent MoE shapes")
+    lib = load_library()
+    need = lib.moe_ffn_fp8_workspace_bytes(T, H, I, E, K)
+    if y is None:
+        y = torch.empty((T, H), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device)
+    rc = lib.moe_ffn_fp8(x.data_ptr(), ids.data_ptr(), wts.data_ptr(), w13.data_ptr(), s13.data_ptr(), w2.data_ptr(),
+                         s2.data_ptr(), y.data_ptr(), T, H, I, E, K, workspace.data_ptr(), workspace.numel(), stream.cuda_stream)
+    if rc != 0:
+        raise AttnError(rc, strerror(rc))
+    return y

@@ -1,4 +1,4 @@
-"""Build the C-ABI library (attention forward, bf16 GEMM) for gfx950 with hipcc, in-tree."""
+"""Build the C-ABI library (attention forward, bf16 GEMM, FP8 MoE) for gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
 import os
@@ -7,7 +7,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libattn_mi355x.so")
-SOURCES = ["attn_api.cpp", "attn_fwd_kernel.hip", "gemm_api.cpp", "gemm_bf16_kernel.hip"]
+SOURCES = ["attn_api.cpp", "attn_fwd_kernel.hip", "gemm_api.cpp", "gemm_bf16_kernel.hip",
+           "moe_api.cpp", "moe_fp8_kernel.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 instructions are kept out of all device code on the test machines

@@ -1,0 +1,369 @@
+// Fused mixture-of-experts feed-forward in block-quantized FP8 for gfx950 (MI355X): the
+// paper's fused-MoE workload (Section 8; Section 8.1 "Fused MoE": tokens and experts are
+// partitioned, tokens reach their experts through sorted maps, blockwise quantization is
+// preserved, the up-projection intermediates are quantized to FP8 so that both projections run
+// on the FP8 matrix cores).
+//
+// Five kernels on one stream, all state in the caller's workspace:
+//   moe_route     counting sort of the local (token, slot) pairs by expert: sorted rows, the
+//                 inverse map, and the list of 64-row tiles (expert, first row, rows);
+//   moe_quant_x   activation quantization, one group of 128 features per 32 lanes;
+//   moe_gemm<UP>  per (row tile, 128 intermediate columns): gate and up products on
+//                 v_mfma_scale_f32_32x32x64_f8f6f4, block scales applied per 128-deep stage,
+//                 SiLU gate, requantization of the 128-column group, FP8 store;
+//   moe_gemm<DN>  per (row tile, 256 output columns): down product, fp32 rows to the workspace;
+//   moe_combine   y[t] = sum over local slots of weight * row, rounded once to bf16.
+// With 16 to 256 rows per expert the products are bound by streaming the expert weights from
+// HBM (each byte is used for 2 x rows FLOPs), so the grouped product keeps three 40 KB stages
+// of direct-to-LDS copies in flight per workgroup and does nothing clever with the MFMAs.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_layout.h"
+#include "moe_launch.h"
+
+namespace {
+
+using namespace gemm_layout;   // kt_*: the 128-byte-row swizzled tile of the bf16 GEMM, here 128 e4m3 per row
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+#define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
+
+template <int V> struct IntC { static constexpr int value = V; };
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (BEGIN < END) {
+        f(IntC<BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
+}
+
+// Asynchronous 16-byte-per-lane copy HBM -> LDS (lane i's bytes land at lds_addr + IMM + 16 i);
+// inline asm so that the compiler's wait-count pass does not tie later LDS reads to it; awaited
+// explicitly with s_waitcnt vmcnt before the barrier that publishes the stage.
+template <int IMM>
+__device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_off, unsigned lds_addr) {
+    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(byte_off), "s"(base), "s"(lds_addr), "n"(IMM) : "memory", "scc");
+}
+
+// quant128 on four values of a 32-lane group: returns the four e4m3 codes packed little-endian.
+// scale = amax * (1/448) (1 if amax = 0), code = e4m3(clamp(v * (1/scale))): fp32 throughout, a true
+// division, v_cvt_pk_fp8_f32 rounds to nearest even (checked against the format on the device).
+__device__ __forceinline__ float quant_scale(float amax) { return amax == 0.0f ? 1.0f : amax * (1.0f / 448.0f); }
+__device__ __forceinline__ unsigned quant_pack4(float v0, float v1, float v2, float v3, float inv) {
+    const float c0 = fminf(fmaxf(v0 * inv, -448.0f), 448.0f), c1 = fminf(fmaxf(v1 * inv, -448.0f), 448.0f);
+    const float c2 = fminf(fmaxf(v2 * inv, -448.0f), 448.0f), c3 = fminf(fmaxf(v3 * inv, -448.0f), 448.0f);
+    int p = __builtin_amdgcn_cvt_pk_fp8_f32(c0, c1, 0, false);
+    p = __builtin_amdgcn_cvt_pk_fp8_f32(c2, c3, p, true);
+    return (unsigned)p;
+}
+
+// ------------------------------------------------------------------------------------
+// Routing: one workgroup.  Rows within an expert are in arrival order of the atomics: every
+// row is computed independently and found again through `pos`, so the order does not show.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void moe_route(MoeParams p) {
+    __shared__ int cnt[256], start[257], tstart[257], cur[256];
+    const int tid = threadIdx.x, E = p.E, n = p.T * p.KTOP;
+    for (int e = tid; e < 256; e += 1024) cnt[e] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += 1024) {
+        const int e = p.ids[i];
+        if (e >= 0 && e < E) atomicAdd(&cnt[e], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int rows = 0, tiles = 0;
+        for (int e = 0; e < E; ++e) {
+            start[e] = rows; tstart[e] = tiles;
+            rows += cnt[e]; tiles += (cnt[e] + kMoeBM - 1) / kMoeBM;
+        }
+        start[E] = rows; tstart[E] = tiles;
+        p.ntiles[0] = tiles;
+    }
+    __syncthreads();
+    for (int e = tid; e <= E; e += 1024) p.offsets[e] = start[e];
+    for (int e = tid; e < E; e += 1024) {
+        cur[e] = start[e];
+        const int nt = tstart[e + 1] - tstart[e];
+        for (int m = 0; m < nt; ++m) {
+            p.tile_expert[tstart[e] + m] = e;
+            p.tile_row0[tstart[e] + m] = start[e] + m * kMoeBM;
+            p.tile_rows[tstart[e] + m] = min(kMoeBM, cnt[e] - m * kMoeBM);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < n; i += 1024) {
+        const int e = p.ids[i];
+        int r = -1;
+        if (e >= 0 && e < E) {
+            r = atomicAdd(&cur[e], 1);
+            p.sorted_tok[r] = i / p.KTOP;
+        }
+        p.pos[i] = r;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Activation quantization: 32 lanes per group of 128 features, 4 features per lane.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void moe_quant_x(MoeParams p) {
+    const long long g = (long long)blockIdx.x * 8 + (threadIdx.x >> 5);
+    const long long groups = (long long)p.T * (p.H / 128);
+    if (g >= groups) return;
+    const int l = threadIdx.x & 31;
+    const u32x2 raw = *(const u32x2*)(p.x + g * 128 + l * 4);
+    const float v0 = __uint_as_float(raw[0] << 16), v1 = __uint_as_float(raw[0] & 0xffff0000u);
+    const float v2 = __uint_as_float(raw[1] << 16), v3 = __uint_as_float(raw[1] & 0xffff0000u);
+    float amax = fmaxf(fmaxf(fabsf(v0), fabsf(v1)), fmaxf(fabsf(v2), fabsf(v3)));
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 32));
+    const float scale = quant_scale(amax);
+    const float inv = 1.0f / scale;
+    *(unsigned*)(p.xq + g * 128 + l * 4) = quant_pack4(v0, v1, v2, v3, inv);
+    if (l == 0) p.xs[g] = scale;
+}
+
+// ------------------------------------------------------------------------------------
+// Grouped block-scaled FP8 product.  Workgroup = 8 wavefronts = 4 (n) x 2 (m): 256 weight rows x
+// 64 routed rows; wavefront (wn, wm): weight rows 64 wn .. +63 as two 32-row MFMA operands,
+// routed rows 32 wm .. +31 in the lanes (transposed product, as in the bf16 GEMM).
+//   UP:  the 256 weight rows of column tile nt are, per wavefront, 32 gate rows j and the 32 up
+//        rows I + j of the same j: both accumulators of a lane meet the same (row, j).
+//   DN:  256 consecutive rows of w2.
+// One stage = 128 bytes of k for all rows (8 KB routed rows + 32 KB weights), three stages in LDS;
+// per stage two K = 64 MFMAs per operand pair into a fresh partial, then acc += partial *
+// (row scale of the stage) * (weight block scale of the stage).
+// ------------------------------------------------------------------------------------
+constexpr int kMoeBN = 256, kMoeStages = 3;
+constexpr int kMoeStageA = kMoeBM * 128, kMoeStageB = kMoeBN * 128, kMoeStage = kMoeStageA + kMoeStageB;
+constexpr int kMoeMaxKB = 64;                       // 128-blocks along k: H, I <= 8192
+constexpr int kMoeSaPitch = kMoeMaxKB + 1;          // floats per row of the row-scale table (odd: no bank conflicts)
+
+template <bool UP>
+__global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
+    __shared__ __attribute__((aligned(16))) char smem[kMoeStages * kMoeStage];
+    __shared__ float sa_tab[kMoeBM * kMoeSaPitch];   // row scale of every routed row and stage
+    __shared__ float sb_tab[2 * kMoeMaxKB];          // weight block scale of the tile's two 128-row blocks and every stage
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave & 3, wm = wave >> 2;
+    const int half = lane >> 5;
+
+    // workgroup -> (row tile mt, column tile nt); XCD-aware: consecutive logical ids (the row
+    // tiles of one expert, same nt, share their weight tile) stay on one XCD and its L2
+    const int nblocks = gridDim.x, bid = blockIdx.x;
+    const int per_xcd = nblocks >> 3;
+    const int logical = (bid < per_xcd * 8) ? (bid & 7) * per_xcd + (bid >> 3) : bid;
+    const int nt = logical / p.max_tiles, mt = logical - nt * p.max_tiles;
+    if (mt >= p.ntiles[0]) return;                  // uniform: before any barrier
+
+    const int e = p.tile_expert[mt], row0 = p.tile_row0[mt], rows = p.tile_rows[mt];
+    const int KB = UP ? p.H : p.I;                  // bytes (= elements) per row of both operands
+    const int nK = KB >> 7;
+    const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
+
+    // ---- copies: per stage this wavefront issues instruction `wave` of the 8 of the routed rows
+    // and instructions wave + 8 n (n = 0..3) of the 32 of the weights ----
+    unsigned a_off, b_off[4];
+    {
+        const int r = min(kt_dma_row(wave, lane), rows - 1);          // rows past the tile re-read its last row
+        const int src = UP ? p.sorted_tok[row0 + r] : row0 + r;
+        a_off = (unsigned)src * (unsigned)KB + 16u * (unsigned)kt_dma_chunk(wave, lane);
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            const int i = wave + 8 * n, tr = kt_dma_row(i, lane);
+            int wrow;
+            if (UP) wrow = ((tr & 63) >> 5) * p.I + nt * 128 + ((tr >> 6) << 5) + (tr & 31);
+            else wrow = min(nt * kMoeBN + tr, p.H - 1);               // rows past H re-read the last one
+            b_off[n] = (unsigned)wrow * (unsigned)KB + 16u * (unsigned)kt_dma_chunk(i, lane);
+        }
+    }
+    const char* const a_base = UP ? (const char*)p.xq : (const char*)p.aq;
+    const char* const b_base = UP ? (const char*)(p.w13 + (size_t)e * 2 * (size_t)p.I * (size_t)p.H)
+                                  : (const char*)(p.w2 + (size_t)e * (size_t)p.H * (size_t)p.I);
+    const unsigned lds_copy_base = lds_base + wave * 1024;
+    auto dma_stage = [&](int U, auto sc) __attribute__((always_inline)) {
+        constexpr int s = decltype(sc)::value;
+        dma_to_lds_16B<s * kMoeStage>(a_base + (size_t)U * 128, a_off, lds_copy_base);
+        static_for<0, 4>([&](auto n) __attribute__((always_inline)) {
+            dma_to_lds_16B<s * kMoeStage + kMoeStageA + n.value * 8192>(b_base + (size_t)U * 128, b_off[n.value], lds_copy_base);
+        });
+    };
+
+    // ---- row scales of all stages into LDS ----
+    {
+        const float* const src = UP ? p.xs : p.as;
+        for (int idx = tid; idx < kMoeBM * nK; idx += 512) {
+            const int m = idx / nK, b = idx - m * nK;
+            const int r = min(m, rows - 1);
+            const int srow = UP ? p.sorted_tok[row0 + r] : row0 + r;
+            sa_tab[m * kMoeSaPitch + b] = src[(size_t)srow * nK + b];
+        }
+    }
+    // ---- weight block scales of all stages into LDS (read back as wavefront-uniform broadcasts; a
+    // global load here would make the compiler wait for the copies in flight at every use) ----
+    if (tid < 2 * nK) {
+        const int which = tid / nK, b = tid - which * nK;
+        const float* src;
+        if (UP) src = p.s13 + ((size_t)e * 2 * (p.I >> 7) + (which ? (p.I >> 7) : 0) + nt) * nK;   // gate rows, up rows of block nt
+        else src = p.s2 + ((size_t)e * (p.H >> 7) + min(nt * 2 + which, (p.H >> 7) - 1)) * nK;
+        sb_tab[which * kMoeMaxKB + b] = src[b];
+    }
+    const int sb_sel0 = UP ? 0 : (wn >> 1), sb_sel1 = UP ? 1 : (wn >> 1);
+
+    // ---- per-lane LDS read addresses (stage 0): K = 64 operand = 32 bytes = chunks 4 ks + 2 half + {0,1} ----
+    unsigned a_addr[2][2], b_addr[2][2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            a_addr[ks][q] = lds_base + kt_offset(32 * wm + (lane & 31), 4 * ks + 2 * half + q);
+            b_addr[ks][q] = lds_base + kMoeStageA + kt_offset(64 * wn + (lane & 31), 4 * ks + 2 * half + q);
+        }
+    auto frag = [&](unsigned addr0, unsigned addr1, int imm) __attribute__((always_inline)) -> i32x8 {
+        const i32x4 lo = *LDS_PTR(i32x4, (size_t)(addr0 + imm));
+        const i32x4 hi = *LDS_PTR(i32x4, (size_t)(addr1 + imm));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    f32x16 acc[2];
+#pragma unroll
+    for (int in = 0; in < 2; ++in)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[in][r] = 0.0f;
+
+    auto barrier = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // ---- prologue: two stages in flight ----
+    dma_stage(0, IntC<0>{});
+    if (1 < nK) dma_stage(1, IntC<1>{});
+
+    auto step = [&](int U, auto sc) __attribute__((always_inline)) {
+        constexpr int s = decltype(sc)::value;
+        // stage U has landed once at most the copies of stage U+1 (5 per wavefront) are outstanding
+        if (U + 1 < nK) __builtin_amdgcn_s_waitcnt(0x0075);    // vmcnt(5), lgkmcnt(0)
+        else __builtin_amdgcn_s_waitcnt(0x0070);               // vmcnt(0), lgkmcnt(0)
+        asm volatile("" ::: "memory");
+        barrier();                                             // stage U visible; stage U-1's buffer is free
+        if (U + 2 < nK) dma_stage(U + 2, IntC<(s + 2) % kMoeStages>{});
+        const float sa = sa_tab[(32 * wm + (lane & 31)) * kMoeSaPitch + U];
+        const float sb0 = sb_tab[sb_sel0 * kMoeMaxKB + U], sb1 = sb_tab[sb_sel1 * kMoeMaxKB + U];
+        const i32x8 fa0 = frag(a_addr[0][0], a_addr[0][1], s * kMoeStage);
+        const i32x8 fa1 = frag(a_addr[1][0], a_addr[1][1], s * kMoeStage);
+        const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        static_for<0, 2>([&](auto in) __attribute__((always_inline)) {
+            const i32x8 fb0 = frag(b_addr[0][0], b_addr[0][1], s * kMoeStage + in.value * 4096);
+            const i32x8 fb1 = frag(b_addr[1][0], b_addr[1][1], s * kMoeStage + in.value * 4096);
+            f32x16 part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb0, fa0, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+            part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb1, fa1, part, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+            const float f = sa * (in.value == 0 ? sb0 : sb1);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[in.value][r] = fmaf(part[r], f, acc[in.value][r]);
+        });
+    };
+    for (int U = 0;;) {
+        step(U, IntC<0>{}); if (++U >= nK) break;
+        step(U, IntC<1>{}); if (++U >= nK) break;
+        step(U, IntC<2>{}); if (++U >= nK) break;
+    }
+
+    // result layout of a lane: register r of operand `in` is weight row 32 in + 8 (r/4) + 4 half + r%4
+    // of the wavefront's 64, routed row 32 wm + lane%32
+    const int m = 32 * wm + (lane & 31);
+    if constexpr (UP) {
+        // SiLU gate, then quant128 over the tile's 128 columns of each routed row
+        float h[16];
+        float amax = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float g = acc[0][r];
+            h[r] = g / (1.0f + __expf(-g)) * acc[1][r];
+            amax = fmaxf(amax, fabsf(h[r]));
+        }
+        {   // across the two halves of the wavefront (rows 4 half + ..)
+            const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
+            const unsigned s0 = sw[0], s1 = sw[1];
+            amax = fmaxf(__uint_as_float(s0), __uint_as_float(s1));
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        barrier();                                             // every wavefront is done with the stage buffers
+        float* const ex = (float*)smem;                        // [wm][wn][32]
+        if (half == 0) ex[(wm * 4 + wn) * 32 + (lane & 31)] = amax;
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        barrier();
+#pragma unroll
+        for (int w = 0; w < 4; ++w) amax = fmaxf(amax, ex[(wm * 4 + w) * 32 + (lane & 31)]);
+        const float scale = quant_scale(amax);
+        const float inv = 1.0f / scale;
+        if (m < rows) {
+            uint8_t* const dst = p.aq + (size_t)(row0 + m) * p.I + nt * 128 + 32 * wn + 4 * half;
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4)
+                *(unsigned*)(dst + 8 * g4) = quant_pack4(h[4 * g4], h[4 * g4 + 1], h[4 * g4 + 2], h[4 * g4 + 3], inv);
+            if (wn == 0 && half == 0) p.as[(size_t)(row0 + m) * (p.I >> 7) + nt] = scale;
+        }
+    } else {
+        if (m < rows) {
+#pragma unroll
+            for (int in = 0; in < 2; ++in)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int c = nt * kMoeBN + 64 * wn + 32 * in + 8 * g4 + 4 * half;
+                    if (c < p.H) {
+                        const f32x4 v = {acc[in][4 * g4], acc[in][4 * g4 + 1], acc[in][4 * g4 + 2], acc[in][4 * g4 + 3]};
+                        *(f32x4*)(p.o + (size_t)(row0 + m) * p.H + c) = v;
+                    }
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Combine: y[t][c] = sum over local slots k (ascending) of wts[t][k] * o[pos[t][k]][c], bf16.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void moe_combine(MoeParams p) {
+    const int cblocks = (p.H / 8 + 255) / 256;
+    const int t = blockIdx.x / cblocks;
+    const int c = ((blockIdx.x - t * cblocks) * 256 + threadIdx.x) * 8;
+    if (c >= p.H) return;
+    float acc[8] = {};
+    for (int k = 0; k < p.KTOP; ++k) {
+        const int r = p.pos[t * p.KTOP + k];
+        if (r < 0) continue;
+        const float w = p.wts[t * p.KTOP + k];
+        const f32x4 a = *(const f32x4*)(p.o + (size_t)r * p.H + c), b = *(const f32x4*)(p.o + (size_t)r * p.H + c + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { acc[i] = fmaf(w, a[i], acc[i]); acc[4 + i] = fmaf(w, b[i], acc[4 + i]); }
+    }
+    typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+    bf16x8 out;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[i] = (__bf16)acc[i];
+    *(bf16x8*)(p.y + (size_t)t * p.H + c) = out;
+}
+
+}  // namespace
+
+int moe_launch(const MoeParams& p, hipStream_t stream) {
+    hipLaunchKernelGGL(moe_route, dim3(1), dim3(1024), 0, stream, p);
+    const long long groups = (long long)p.T * (p.H / 128);
+    hipLaunchKernelGGL(moe_quant_x, dim3((unsigned)((groups + 7) / 8)), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((moe_gemm<true>), dim3((unsigned)(p.max_tiles * (p.I / 128))), dim3(512), 0, stream, p);
+    hipLaunchKernelGGL((moe_gemm<false>), dim3((unsigned)(p.max_tiles * ((p.H + kMoeBN - 1) / kMoeBN))), dim3(512), 0, stream, p);
+    hipLaunchKernelGGL(moe_combine, dim3((unsigned)(((p.H / 8 + 255) / 256) * p.T)), dim3(256), 0, stream, p);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}

@@ -1,0 +1,34 @@
+// Internal interface between the C-ABI translation unit (argument checks, workspace layout,
+// no device code) and the MoE kernel translation unit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+constexpr int kMoeBM = 64;   // rows (routed token slots of one expert) per tile of the grouped products
+
+struct MoeParams {
+    const __bf16* x; const int* ids; const float* wts;
+    const uint8_t* w13; const float* s13; const uint8_t* w2; const float* s2;
+    __bf16* y;
+    int T, H, I, E, KTOP;
+    int max_tiles;            // upper bound on the number of row tiles: ceil(T*KTOP / kMoeBM) + E
+    // workspace carve-up (all device pointers into the caller's workspace)
+    int* offsets;             // [E + 1] first sorted row of each expert
+    int* cursor;              // [E]     scatter cursors
+    int* ntiles;              // [1]     row tiles in use
+    int* tile_expert;         // [max_tiles]
+    int* tile_row0;           // [max_tiles] first sorted row of the tile
+    int* tile_rows;           // [max_tiles] rows in the tile (1..kMoeBM)
+    int* sorted_tok;          // [T*KTOP] token of each sorted row
+    int* pos;                 // [T*KTOP] sorted row of slot (t, k), or -1 if the slot is not local
+    uint8_t* xq; float* xs;   // [T, H] codes, [T, H/128] scales
+    uint8_t* aq; float* as;   // [T*KTOP, I] codes, [T*KTOP, I/128] scales of the intermediate
+    float* o;                 // [T*KTOP, H] down-projection rows
+};
+
+// Byte offsets of the workspace parts for given sizes; returns the total.
+size_t moe_workspace_layout(int T, int H, int I, int E, int KTOP, size_t off[13]);
+
+// Enqueue the whole path on `stream`.  Returns 0, or -1 if a launch was refused.
+int moe_launch(const MoeParams& p, hipStream_t stream);

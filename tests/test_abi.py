@@ -136,3 +136,38 @@ def test_gemm_argument_errors_are_reported_without_a_gpu(lib):
     assert g(a=A16 + 1) == -4 and g(c=A16 + 3) == -4  # odd addresses cannot hold bf16
     assert lib.gemm_bf16_tile(A16, A16, A16, 256, 256, 64, 64, 256, 256, 0, 64, None) == -3   # tile must be 0, 128 or 256
     assert lib.gemm_bf16_tile(None, A16, A16, 256, 256, 64, 64, 256, 256, 0, 128, None) == -1
+
+
+# ---------------------------------------------------------------------------------------------
+# moe.h
+# ---------------------------------------------------------------------------------------------
+MOE_HEADER = os.path.join(ROOT, "include", "moe.h")
+
+
+def test_moe_header_symbols_are_exported(lib):
+    src = re.sub(r"/\*.*?\*/", "", open(MOE_HEADER).read(), flags=re.S)
+    names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", src)
+    assert set(names) == {"moe_ffn_fp8", "moe_ffn_fp8_workspace_bytes", "moe_ffn_fp8_workspace_offset", "moe_ffn_fp8_flops_per_pair"}
+    for name in names:
+        assert hasattr(lib, name), name
+    assert lib.moe_ffn_fp8_flops_per_pair(7168, 2048) == 6.0 * 7168 * 2048
+
+
+def test_moe_workspace_size_and_argument_errors(lib):
+    need = lib.moe_ffn_fp8_workspace_bytes(1024, 7168, 2048, 32, 4)
+    slots = 1024 * 4
+    assert need >= slots * 7168 * 4 + slots * 2048 + 1024 * 7168 and need % 256 == 0     # rows, codes of both activations
+    assert lib.moe_ffn_fp8_workspace_bytes(1024, 7168 + 64, 2048, 32, 4) == 0            # H not a multiple of 128
+    assert lib.moe_ffn_fp8_workspace_bytes(1 << 19, 7168, 2048, 32, 4) == 0              # too many slots
+    offs = [lib.moe_ffn_fp8_workspace_offset(1024, 7168, 2048, 32, 4, part) for part in range(13)]
+    assert offs[0] == 0 and all(b > a and b % 256 == 0 for a, b in zip(offs, offs[1:])) and offs[12] + slots * 7168 * 4 <= need
+    assert lib.moe_ffn_fp8_workspace_offset(1024, 7168, 2048, 32, 4, 13) == -1 and lib.moe_ffn_fp8_workspace_offset(0, 7168, 2048, 32, 4, 0) == -1
+
+    def m(x=A16, ids=A16, wts=A16, w13=A16, s13=A16, w2=A16, s2=A16, y=A16, T=64, H=256, I=128, E=4, K=2, ws=A16, wsb=1 << 30):
+        return lib.moe_ffn_fp8(x, ids, wts, w13, s13, w2, s2, y, T, H, I, E, K, ws, wsb, None)
+
+    for name in ("x", "ids", "wts", "w13", "s13", "w2", "s2", "y", "ws"):
+        assert m(**{name: None}) == -1, name
+    for kw in (dict(T=0), dict(H=100), dict(I=0), dict(E=0), dict(E=257), dict(K=17), dict(H=8192 + 128), dict(wsb=1024)):
+        assert m(**kw) == -2, kw
+    assert m(x=A16 + 2) == -4 and m(ws=A16 + 16) == -4 and m(ids=A16 + 1) == -4

@@ -148,6 +148,29 @@ def test_slot_order_does_not_matter_and_zero_gates_give_zero():
     assert oracle.moe_ref(**d).any()
 
 
+def test_staged_entry_points_compose_to_the_whole():
+    """intermediate -> fp32 -> quant128 -> down -> weighted sum reproduces moe_ref; the intermediate also
+    matches the dequantize-then-matmul formulation."""
+    w, d = small(T=6, seed=12, EP=1, H=256, I=256)
+    y = oracle.moe_ref(**d)
+    t = 4
+    want = np.zeros(w.H)
+    for k in range(w.KTOP):
+        e = int(d["ids"][t, k])
+        a = oracle.moe_intermediate(d["x"], d["w13"], d["s13"], t, e)
+        codes, scales = zip(*[oracle.quant_group(a[128 * b:128 * b + 128].astype(np.float32)) for b in range(w.I // 128)])
+        want += float(d["wts"][t, k]) * oracle.moe_down(np.concatenate(codes), np.array(scales, dtype=np.float32), d["w2"], d["s2"], e)
+    np.testing.assert_allclose(want, y[t], rtol=1e-13, atol=1e-15)
+    # the intermediate against plain dequantized matmuls
+    xf = I.bf16_bits_to_f32(d["x"][t])
+    xd = np.concatenate([VALS[c] * s for c, s in (oracle.quant_group(xf[128 * b:128 * b + 128]) for b in range(w.H // 128))])
+    e = int(d["ids"][t, 0])
+    w13 = VALS[d["w13"][e]] * np.repeat(np.repeat(d["s13"][e].astype(np.float64), 128, axis=0), 128, axis=1)
+    gu = w13 @ xd
+    np.testing.assert_allclose(oracle.moe_intermediate(d["x"], d["w13"], d["s13"], t, e),
+                               gu[:w.I] / (1 + np.exp(-gu[:w.I])) * gu[w.I:], rtol=1e-10, atol=1e-13)
+
+
 def test_workload_table_and_generator():
     w = I.MOE_WORKLOADS["M1024"]
     assert (w.T, w.H, w.I, w.E, w.KTOP, w.EP) == (1024, 7168, 2048, 32, 4, 8)

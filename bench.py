@@ -5,7 +5,9 @@
 
 --workload takes an attention workload (C1..C5, P1024..P16384, N8K; default C3, the headline)
 or a GEMM workload (G1024..G16384: C = A B with B stored [K,N]; G1024T..: B stored [N,K]);
-for GEMM a step is one gemm_bf16 call and FLOPs are 2*M*N*K.
+for GEMM a step is one gemm_bf16 call and FLOPs are 2*M*N*K.  M1024..M16384 are the fused-MoE
+workloads (tokens; H=7168, I=2048, top-4 of 256 experts, 32 local): a step is one moe_ffn_fp8
+call, FLOPs are 6*H*I per routed (token, local expert) pair, and the roofline is HBM.
 
 A step is one attn_fwd call (the whole hot path: Q/K/V tile loads, QK^T, online
 softmax, PV, O/LSE stores) on one batch of seeded synthetic input that is already
@@ -145,6 +147,85 @@ def bench_gemm(args, torch, lib, binding, I, dev) -> int:
     return 0 if (parity is None or parity["ok"]) else 4
 
 
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E (published)
+
+
+def bench_moe(args, torch, lib, binding, I, dev) -> int:
+    w = I.MOE_WORKLOADS[args.workload]
+    d = I.make_moe(w)
+    t = {"x": torch.from_numpy(d["x"].view(np.int16)).view(torch.bfloat16).to(dev)}
+    for k in ("ids", "wts", "w13", "s13", "w2", "s2"):
+        t[k] = torch.from_numpy(d[k]).to(dev)
+    y = torch.full((w.T, w.H), float("nan"), dtype=torch.bfloat16, device=dev)
+    need = lib.moe_ffn_fp8_workspace_bytes(w.T, w.H, w.I, w.E, w.KTOP)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev)
+    sp = stream.cuda_stream
+    argv = (t["x"].data_ptr(), t["ids"].data_ptr(), t["wts"].data_ptr(), t["w13"].data_ptr(), t["s13"].data_ptr(),
+            t["w2"].data_ptr(), t["s2"].data_ptr(), y.data_ptr(), w.T, w.H, w.I, w.E, w.KTOP, ws.data_ptr(), need)
+
+    def step():
+        rc = lib.moe_ffn_fp8(*argv, sp)
+        if rc != 0:
+            raise RuntimeError(binding.strerror(rc))
+
+    def up_only():                        # the dominant kernel alone (stage 2: gate/up product), on the state left by a full call
+        rc = lib.moe_ffn_fp8_stages(*argv, 2, 2, sp)
+        if rc != 0:
+            raise RuntimeError(binding.strerror(rc))
+
+    ms_per_step, path_ms = time_steps(torch, step, stream, args.steps, args.warmup)
+    _, up_ms = time_steps(torch, up_only, stream, args.steps, max(3, args.warmup // 4))
+    step()                                # leave y and the workspace as a full call leaves them
+    torch.cuda.synchronize()
+
+    ids = d["ids"]
+    pairs = w.local_slots(ids)
+    used = len(set(ids[ids >= 0].tolist()))
+    flops = lib.moe_ffn_fp8_flops_per_pair(w.H, w.I) * pairs
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    # algorithmic bytes of the gate/up kernel: the used experts' w13 once, one quantized row in and one out per pair, scales
+    up_bytes = used * (2.0 * w.I * w.H + 4.0 * (2 * w.I // 128) * (w.H // 128)) + pairs * (w.H + 4.0 * w.H / 128 + w.I + 4.0 * w.I / 128)
+    achieved = up_bytes / (up_ms * 1e-3) / 1e9
+
+    cpu = parity = None
+    if not args.no_cpu_baseline:
+        from oracle import moe_ref
+        rows = I.sample_tokens(w, ids, 16)
+        c0 = time.perf_counter()
+        ref = moe_ref(rows=rows, **d)
+        cpu_s = time.perf_counter() - c0
+        got = I.bf16_bits_to_f32(y[torch.from_numpy(rows.astype(np.int64)).to(dev)].view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+        live = ref.any(axis=1)
+        rel = np.sqrt(((got - ref)[live] ** 2).sum(axis=1) / (ref[live] ** 2).sum(axis=1)) if live.any() else np.zeros(1)
+        parity = {"row_rel_l2_max": float(rel.max()), "row_rel_l2_median": float(np.median(rel)), "tokens_checked": int(rows.size),
+                  "note": "end-to-end net only (requantization decisions are not unique); the staged bounds are in tests/test_moe_parity_gpu.py",
+                  "ok": bool(np.isfinite(got).all() and rel.max() < 0.06 and np.median(rel) < 5e-3 and not got[~live].any())}
+        cpu_pairs = int((ids[rows] >= 0).sum())
+        cpu = {"value": 6.0 * w.H * w.I * cpu_pairs / cpu_s / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+               "sample": "%d seeded tokens (%d local pairs) of %s, %.1f s" % (rows.size, cpu_pairs, w.name, cpu_s)}
+
+    prop = torch.cuda.get_device_properties(dev)
+    out = {
+        "metric": "fused MoE FP8 TFLOP/s (6*H*I per routed pair) and % of HBM peak of its dominant kernel",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8_e4m3", "data": "synthetic",
+        "config": {"workload": "%s: T=%d tokens, H=%d, I=%d, top-%d of %d experts, %d local, seed %d: %d local pairs on %d experts"
+                               % (w.name, w.T, w.H, w.I, w.KTOP, w.E * w.EP, w.E, w.seed, pairs, used),
+                   "flops_per_step": flops, "flop_convention": "6*H*I per routed (token, local expert) pair"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
+                     "traffic": read_traffic(w.name, "moe_gemm_up"), "kernel": "moe_gemm<UP> (stage 2 of 5)", "kernel_ms": up_ms,
+                     "algorithmic_bytes": up_bytes, "path_ms": path_ms,
+                     "path_algorithmic_gbs": w.bytes(ids) / (path_ms * 1e-3) / 1e9},
+        "cpu_baseline": cpu,
+        "parity": parity,
+        "device": {"name": prop.name, "cus": prop.multi_processor_count, "clock_mhz": getattr(prop, "clock_rate", 0) / 1e3 or None},
+    }
+    print(json.dumps(out))
+    return 0 if (parity is None or parity["ok"]) else 4
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,6 +265,8 @@ def main() -> int:
 
     if args.workload in I.GEMM_WORKLOADS:
         return bench_gemm(args, torch, lib, binding, I, dev)
+    if args.workload in I.MOE_WORKLOADS:
+        return bench_moe(args, torch, lib, binding, I, dev)
     w = I.WORKLOADS[args.workload]
     qb, kb, vb = I.make_qkv(w)
     to_dev = lambda a: torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)

@@ -48,6 +48,8 @@ def load_library(build_if_missing: bool = True):
         lib.moe_ffn_fp8_workspace_offset.argtypes = [i, i, i, i, i, i]
         lib.moe_ffn_fp8.restype = i
         lib.moe_ffn_fp8.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, p, ctypes.c_size_t, p]
+        lib.moe_ffn_fp8_stages.restype = i
+        lib.moe_ffn_fp8_stages.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, p, ctypes.c_size_t, i, i, p]
         lib.moe_ffn_fp8_flops_per_pair.restype = ctypes.c_double
         lib.moe_ffn_fp8_flops_per_pair.argtypes = [i, i]
         lib.attn_strerror.restype = ctypes.c_char_p

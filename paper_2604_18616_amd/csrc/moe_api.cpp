@@ -51,10 +51,11 @@ extern "C" long long moe_ffn_fp8_workspace_offset(int T, int H, int I, int E, in
     return (long long)off[part];
 }
 
-extern "C" int moe_ffn_fp8(const void* x, const int* ids, const float* wts,
-                           const void* w13, const float* s13, const void* w2, const float* s2,
-                           void* y, int T, int H, int I, int E, int KTOP,
-                           void* workspace, size_t workspace_bytes, void* stream) {
+extern "C" int moe_ffn_fp8_stages(const void* x, const int* ids, const float* wts,
+                                  const void* w13, const float* s13, const void* w2, const float* s2,
+                                  void* y, int T, int H, int I, int E, int KTOP,
+                                  void* workspace, size_t workspace_bytes, int first_stage, int last_stage, void* stream) {
+    if (first_stage < 0 || last_stage > 4 || first_stage > last_stage) return ATTN_ERR_UNSUPPORTED;
     if (!x || !ids || !wts || !w13 || !s13 || !w2 || !s2 || !y || !workspace) return ATTN_ERR_NULL_PTR;
     if (!sizes_ok(T, H, I, E, KTOP)) return ATTN_ERR_BAD_SHAPE;
     size_t off[13];
@@ -77,7 +78,14 @@ extern "C" int moe_ffn_fp8(const void* x, const int* ids, const float* wts,
     p.xq = (uint8_t*)(ws + off[8]); p.xs = (float*)(ws + off[9]);
     p.aq = (uint8_t*)(ws + off[10]); p.as = (float*)(ws + off[11]);
     p.o = (float*)(ws + off[12]);
-    return moe_launch(p, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+    return moe_launch(p, first_stage, last_stage, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+extern "C" int moe_ffn_fp8(const void* x, const int* ids, const float* wts,
+                           const void* w13, const float* s13, const void* w2, const float* s2,
+                           void* y, int T, int H, int I, int E, int KTOP,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+    return moe_ffn_fp8_stages(x, ids, wts, w13, s13, w2, s2, y, T, H, I, E, KTOP, workspace, workspace_bytes, 0, 4, stream);
 }
 
 extern "C" double moe_ffn_fp8_flops_per_pair(int H, int I) {

@@ -358,12 +358,13 @@ __global__ __launch_bounds__(256) void moe_combine(MoeParams p) {
 
 }  // namespace
 
-int moe_launch(const MoeParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL(moe_route, dim3(1), dim3(1024), 0, stream, p);
+int moe_launch(const MoeParams& p, int first, int last, hipStream_t stream) {
+    auto on = [&](int stage) { return first <= stage && stage <= last; };
+    if (on(0)) hipLaunchKernelGGL(moe_route, dim3(1), dim3(1024), 0, stream, p);
     const long long groups = (long long)p.T * (p.H / 128);
-    hipLaunchKernelGGL(moe_quant_x, dim3((unsigned)((groups + 7) / 8)), dim3(256), 0, stream, p);
-    hipLaunchKernelGGL((moe_gemm<true>), dim3((unsigned)(p.max_tiles * (p.I / 128))), dim3(512), 0, stream, p);
-    hipLaunchKernelGGL((moe_gemm<false>), dim3((unsigned)(p.max_tiles * ((p.H + kMoeBN - 1) / kMoeBN))), dim3(512), 0, stream, p);
-    hipLaunchKernelGGL(moe_combine, dim3((unsigned)(((p.H / 8 + 255) / 256) * p.T)), dim3(256), 0, stream, p);
+    if (on(1)) hipLaunchKernelGGL(moe_quant_x, dim3((unsigned)((groups + 7) / 8)), dim3(256), 0, stream, p);
+    if (on(2)) hipLaunchKernelGGL((moe_gemm<true>), dim3((unsigned)(p.max_tiles * (p.I / 128))), dim3(512), 0, stream, p);
+    if (on(3)) hipLaunchKernelGGL((moe_gemm<false>), dim3((unsigned)(p.max_tiles * ((p.H + kMoeBN - 1) / kMoeBN))), dim3(512), 0, stream, p);
+    if (on(4)) hipLaunchKernelGGL(moe_combine, dim3((unsigned)(((p.H / 8 + 255) / 256) * p.T)), dim3(256), 0, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }

@@ -30,5 +30,6 @@ struct MoeParams {
 // Byte offsets of the workspace parts for given sizes; returns the total.
 size_t moe_workspace_layout(int T, int H, int I, int E, int KTOP, size_t off[13]);
 
-// Enqueue the whole path on `stream`.  Returns 0, or -1 if a launch was refused.
-int moe_launch(const MoeParams& p, hipStream_t stream);
+// Enqueue stages first..last of the path (0 route, 1 quantize x, 2 gate/up, 3 down, 4 combine) on
+// `stream`.  Returns 0, or -1 if a launch was refused.
+int moe_launch(const MoeParams& p, int first, int last, hipStream_t stream);

@@ -170,7 +170,7 @@ def bench_moe(args, torch, lib, binding, I, dev) -> int:
             raise RuntimeError(binding.strerror(rc))
 
     def up_only():                        # the dominant kernel alone (stage 2: gate/up product), on the state left by a full call
-        rc = lib.moe_ffn_fp8_stages(*argv, 2, 2, sp)
+        rc = lib.moe_ffn_fp8_ex(*argv, 2, 2, 0, sp)
         if rc != 0:
             raise RuntimeError(binding.strerror(rc))
 

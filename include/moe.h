@@ -57,15 +57,19 @@ int moe_ffn_fp8(const void *x, const int *ids, const float *wts,
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Stages first_stage..last_stage of the same path only (0 routing, 1 activation quantization, 2 gate/up
- * product with SiLU and requantization, 3 down product, 4 combine), for profiling one stage and for
- * callers that reuse the routing of a previous call: the stages before first_stage must have run on the
- * same arguments and workspace.  moe_ffn_fp8 is stages 0..4.  A range outside 0..4: ATTN_ERR_UNSUPPORTED.
+ * The same path with two choices opened up, for profiling, tuning and tests:
+ *   first_stage..last_stage  run only these stages (0 routing, 1 activation quantization, 2 gate/up product
+ *       with SiLU and requantization, 3 down product, 4 combine); the stages before first_stage must have run
+ *       on the same arguments, workspace and row_tile.  moe_ffn_fp8 is 0..4.
+ *   row_tile  rows of one expert per workgroup of the two products: 64, 128, or 0 = what moe_ffn_fp8 does
+ *       (128 when T*KTOP >= 1024*E, else 64).
+ * A stage range outside 0..4 or another row_tile: ATTN_ERR_UNSUPPORTED.
  */
-int moe_ffn_fp8_stages(const void *x, const int *ids, const float *wts,
-                       const void *w13, const float *s13, const void *w2, const float *s2,
-                       void *y, int T, int H, int I, int E, int KTOP,
-                       void *workspace, size_t workspace_bytes, int first_stage, int last_stage, void *stream);
+int moe_ffn_fp8_ex(const void *x, const int *ids, const float *wts,
+                   const void *w13, const float *s13, const void *w2, const float *s2,
+                   void *y, int T, int H, int I, int E, int KTOP,
+                   void *workspace, size_t workspace_bytes,
+                   int first_stage, int last_stage, int row_tile, void *stream);
 
 /*
  * Where the parts of the workspace lie after a call (byte offset, or -1 for unsupported sizes or an

@@ -48,8 +48,8 @@ def load_library(build_if_missing: bool = True):
         lib.moe_ffn_fp8_workspace_offset.argtypes = [i, i, i, i, i, i]
         lib.moe_ffn_fp8.restype = i
         lib.moe_ffn_fp8.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, p, ctypes.c_size_t, p]
-        lib.moe_ffn_fp8_stages.restype = i
-        lib.moe_ffn_fp8_stages.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, p, ctypes.c_size_t, i, i, p]
+        lib.moe_ffn_fp8_ex.restype = i
+        lib.moe_ffn_fp8_ex.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, p, ctypes.c_size_t, i, i, i, p]
         lib.moe_ffn_fp8_flops_per_pair.restype = ctypes.c_double
         lib.moe_ffn_fp8_flops_per_pair.argtypes = [i, i]
         lib.attn_strerror.restype = ctypes.c_char_p
@@ -165,12 +165,12 @@ def moe_workspace_offset(T, H, I, E, KTOP, part: int) -> int:
     return int(load_library().moe_ffn_fp8_workspace_offset(T, H, I, E, KTOP, part))
 
 
-def moe_ffn_fp8(x, ids, wts, w13, s13, w2, s2, y=None, workspace=None, stream=None):
+def moe_ffn_fp8(x, ids, wts, w13, s13, w2, s2, y=None, workspace=None, stream=None, row_tile=0):
     """Block-quantized FP8 MoE feed-forward of CUDA tensors: x bf16 [T,H]; ids int32 [T,KTOP] (local
     expert or negative); wts fp32 [T,KTOP]; w13 uint8 [E,2I,H] and w2 uint8 [E,H,I] (e4m3 codes);
     s13 fp32 [E,2I/128,H/128]; s2 fp32 [E,H/128,I/128].  y (bf16 [T,H]) and the workspace (uint8, at
     least moe_workspace_bytes(...)) are allocated with torch if not given.  Enqueued on `stream`
-    (default: torch's current stream); no sync."""
+    (default: torch's current stream); no sync.  row_tile: 0 (by size), 64 or 128 (moe_ffn_fp8_ex)."""
     import torch
 
     for t in (x, ids, wts, w13, s13, w2, s2):
@@ -193,8 +193,9 @@ def moe_ffn_fp8(x, ids, wts, w13, s13, w2, s2, y=None, workspace=None, stream=No
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
     if stream is None:
         stream = torch.cuda.current_stream(x.device)
-    rc = lib.moe_ffn_fp8(x.data_ptr(), ids.data_ptr(), wts.data_ptr(), w13.data_ptr(), s13.data_ptr(), w2.data_ptr(),
-                         s2.data_ptr(), y.data_ptr(), T, H, I, E, K, workspace.data_ptr(), workspace.numel(), stream.cuda_stream)
+    rc = lib.moe_ffn_fp8_ex(x.data_ptr(), ids.data_ptr(), wts.data_ptr(), w13.data_ptr(), s13.data_ptr(), w2.data_ptr(),
+                            s2.data_ptr(), y.data_ptr(), T, H, I, E, K, workspace.data_ptr(), workspace.numel(),
+                            0, 4, int(row_tile), stream.cuda_stream)
     if rc != 0:
         raise AttnError(rc, strerror(rc))
     return y

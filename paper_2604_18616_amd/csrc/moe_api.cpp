@@ -51,11 +51,14 @@ extern "C" long long moe_ffn_fp8_workspace_offset(int T, int H, int I, int E, in
     return (long long)off[part];
 }
 
-extern "C" int moe_ffn_fp8_stages(const void* x, const int* ids, const float* wts,
-                                  const void* w13, const float* s13, const void* w2, const float* s2,
-                                  void* y, int T, int H, int I, int E, int KTOP,
-                                  void* workspace, size_t workspace_bytes, int first_stage, int last_stage, void* stream) {
+extern "C" int moe_ffn_fp8_ex(const void* x, const int* ids, const float* wts,
+                              const void* w13, const float* s13, const void* w2, const float* s2,
+                              void* y, int T, int H, int I, int E, int KTOP,
+                              void* workspace, size_t workspace_bytes,
+                              int first_stage, int last_stage, int row_tile, void* stream) {
     if (first_stage < 0 || last_stage > 4 || first_stage > last_stage) return ATTN_ERR_UNSUPPORTED;
+    if (row_tile != 0 && row_tile != 64 && row_tile != 128) return ATTN_ERR_UNSUPPORTED;
+    const int bm_override = row_tile;
     if (!x || !ids || !wts || !w13 || !s13 || !w2 || !s2 || !y || !workspace) return ATTN_ERR_NULL_PTR;
     if (!sizes_ok(T, H, I, E, KTOP)) return ATTN_ERR_BAD_SHAPE;
     size_t off[13];
@@ -71,7 +74,10 @@ extern "C" int moe_ffn_fp8_stages(const void* x, const int* ids, const float* wt
     p.w13 = (const uint8_t*)w13; p.s13 = s13; p.w2 = (const uint8_t*)w2; p.s2 = s2;
     p.y = (__bf16*)y;
     p.T = T; p.H = H; p.I = I; p.E = E; p.KTOP = KTOP;
-    p.max_tiles = (int)(((size_t)T * KTOP + kMoeBM - 1) / kMoeBM + E);
+    // row tile: 128 when the experts would get about 128 rows or more if an eighth of the slots were local
+    // (the usual expert-parallel share), else 64; `bm_override` is for tests
+    p.bm = bm_override ? bm_override : ((long long)T * KTOP >= 1024LL * E ? 128 : 64);
+    p.max_tiles = (int)(((size_t)T * KTOP + p.bm - 1) / p.bm + E);
     p.offsets = (int*)(ws + off[0]); p.cursor = (int*)(ws + off[1]); p.ntiles = (int*)(ws + off[2]);
     p.tile_expert = (int*)(ws + off[3]); p.tile_row0 = (int*)(ws + off[4]); p.tile_rows = (int*)(ws + off[5]);
     p.sorted_tok = (int*)(ws + off[6]); p.pos = (int*)(ws + off[7]);
@@ -85,7 +91,7 @@ extern "C" int moe_ffn_fp8(const void* x, const int* ids, const float* wts,
                            const void* w13, const float* s13, const void* w2, const float* s2,
                            void* y, int T, int H, int I, int E, int KTOP,
                            void* workspace, size_t workspace_bytes, void* stream) {
-    return moe_ffn_fp8_stages(x, ids, wts, w13, s13, w2, s2, y, T, H, I, E, KTOP, workspace, workspace_bytes, 0, 4, stream);
+    return moe_ffn_fp8_ex(x, ids, wts, w13, s13, w2, s2, y, T, H, I, E, KTOP, workspace, workspace_bytes, 0, 4, 0, stream);
 }
 
 extern "C" double moe_ffn_fp8_flops_per_pair(int H, int I) {

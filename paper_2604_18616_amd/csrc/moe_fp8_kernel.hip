@@ -4,17 +4,17 @@
 // preserved, the up-projection intermediates are quantized to FP8 so that both projections run
 // on the FP8 matrix cores).
 //
-// Five kernels on one stream, all state in the caller's workspace:
-//   moe_route     counting sort of the local (token, slot) pairs by expert: sorted rows, the
-//                 inverse map, and the list of 64-row tiles (expert, first row, rows);
-//   moe_quant_x   activation quantization, one group of 128 features per 32 lanes;
+// Five stages in four kernels on one stream, all state in the caller's workspace:
+//   moe_prepare   workgroup 0: counting sort of the local (token, slot) pairs by expert (sorted
+//                 rows, the inverse map, the list of row tiles (expert, first row, rows)); the
+//                 other workgroups: activation quantization, one group of 128 features per 32 lanes;
 //   moe_gemm<UP>  per (row tile, 128 intermediate columns): gate and up products on
 //                 v_mfma_scale_f32_32x32x64_f8f6f4, block scales applied per 128-deep stage,
 //                 SiLU gate, requantization of the 128-column group, FP8 store;
 //   moe_gemm<DN>  per (row tile, 256 output columns): down product, fp32 rows to the workspace;
 //   moe_combine   y[t] = sum over local slots of weight * row, rounded once to bf16.
 // With 16 to 256 rows per expert the products are bound by streaming the expert weights from
-// HBM (each byte is used for 2 x rows FLOPs), so the grouped product keeps three 40 KB stages
+// HBM (each byte is used for 2 x rows FLOPs), so the grouped product keeps three 40-48 KB stages
 // of direct-to-LDS copies in flight per workgroup and does nothing clever with the MFMAs.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -53,6 +53,13 @@ __device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_o
                  :: "v"(byte_off), "s"(base), "s"(lds_addr), "n"(IMM) : "memory", "scc");
 }
 
+// The same with one dword per lane (lane i's 4 bytes land at lds_addr + IMM + 4 i).
+template <int IMM>
+__device__ __forceinline__ void dma_to_lds_4B(const void* base, unsigned byte_off, unsigned lds_addr) {
+    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :: "v"(byte_off), "s"(base), "s"(lds_addr), "n"(IMM) : "memory", "scc");
+}
+
 // quant128 on four values of a 32-lane group: returns the four e4m3 codes packed little-endian.
 // scale = amax * (1/448) (1 if amax = 0), code = e4m3(clamp(v * (1/scale))): fp32 throughout, a true
 // division, v_cvt_pk_fp8_f32 rounds to nearest even (checked against the format on the device).
@@ -69,7 +76,7 @@ __device__ __forceinline__ unsigned quant_pack4(float v0, float v1, float v2, fl
 // Routing: one workgroup.  Rows within an expert are in arrival order of the atomics: every
 // row is computed independently and found again through `pos`, so the order does not show.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void moe_route(MoeParams p) {
+__device__ __forceinline__ void route_block(const MoeParams& p) {
     __shared__ int cnt[256], start[257], tstart[257], cur[256];
     const int tid = threadIdx.x, E = p.E, n = p.T * p.KTOP;
     for (int e = tid; e < 256; e += 1024) cnt[e] = 0;
@@ -83,7 +90,7 @@ __global__ __launch_bounds__(1024) void moe_route(MoeParams p) {
         int rows = 0, tiles = 0;
         for (int e = 0; e < E; ++e) {
             start[e] = rows; tstart[e] = tiles;
-            rows += cnt[e]; tiles += (cnt[e] + kMoeBM - 1) / kMoeBM;
+            rows += cnt[e]; tiles += (cnt[e] + p.bm - 1) / p.bm;
         }
         start[E] = rows; tstart[E] = tiles;
         p.ntiles[0] = tiles;
@@ -95,8 +102,8 @@ __global__ __launch_bounds__(1024) void moe_route(MoeParams p) {
         const int nt = tstart[e + 1] - tstart[e];
         for (int m = 0; m < nt; ++m) {
             p.tile_expert[tstart[e] + m] = e;
-            p.tile_row0[tstart[e] + m] = start[e] + m * kMoeBM;
-            p.tile_rows[tstart[e] + m] = min(kMoeBM, cnt[e] - m * kMoeBM);
+            p.tile_row0[tstart[e] + m] = start[e] + m * p.bm;
+            p.tile_rows[tstart[e] + m] = min(p.bm, cnt[e] - m * p.bm);
         }
     }
     __syncthreads();
@@ -114,8 +121,8 @@ __global__ __launch_bounds__(1024) void moe_route(MoeParams p) {
 // ------------------------------------------------------------------------------------
 // Activation quantization: 32 lanes per group of 128 features, 4 features per lane.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void moe_quant_x(MoeParams p) {
-    const long long g = (long long)blockIdx.x * 8 + (threadIdx.x >> 5);
+__device__ __forceinline__ void quant_x_block(const MoeParams& p, unsigned block) {
+    const long long g = (long long)block * 32 + (threadIdx.x >> 5);
     const long long groups = (long long)p.T * (p.H / 128);
     if (g >= groups) return;
     const int l = threadIdx.x & 31;
@@ -131,26 +138,41 @@ __global__ __launch_bounds__(256) void moe_quant_x(MoeParams p) {
     if (l == 0) p.xs[g] = scale;
 }
 
+// Stages 0 and 1 do not depend on each other: one launch, workgroup 0 routes while the others quantize.
+// `stages` bit 0: routing, bit 1: quantization.
+__global__ __launch_bounds__(1024) void moe_prepare(MoeParams p, int stages) {
+    if (blockIdx.x == 0) {
+        if (stages & 1) route_block(p);
+    } else if (stages & 2) {
+        quant_x_block(p, blockIdx.x - 1);
+    }
+}
+
 // ------------------------------------------------------------------------------------
 // Grouped block-scaled FP8 product.  Workgroup = 8 wavefronts = 4 (n) x 2 (m): 256 weight rows x
-// 64 routed rows; wavefront (wn, wm): weight rows 64 wn .. +63 as two 32-row MFMA operands,
-// routed rows 32 wm .. +31 in the lanes (transposed product, as in the bf16 GEMM).
+// BM routed rows (BM = 64 or 128, chosen on the host from the number of slots per expert);
+// wavefront (wn, wm): weight rows 64 wn .. +63 as two 32-row MFMA operands, routed rows
+// (BM/2) wm .. in the lanes, BM/64 blocks of 32 (transposed product, as in the bf16 GEMM).
 //   UP:  the 256 weight rows of column tile nt are, per wavefront, 32 gate rows j and the 32 up
 //        rows I + j of the same j: both accumulators of a lane meet the same (row, j).
 //   DN:  256 consecutive rows of w2.
-// One stage = 128 bytes of k for all rows (8 KB routed rows + 32 KB weights), three stages in LDS;
-// per stage two K = 64 MFMAs per operand pair into a fresh partial, then acc += partial *
-// (row scale of the stage) * (weight block scale of the stage).
+// One stage = 128 bytes of k for all rows (BM x 128 routed + 32 KB weights) plus the stage's row
+// scales (one dword copy per wavefront), three stages in LDS; per stage two K = 64 MFMAs per
+// operand pair into a fresh partial, then acc += partial * (row scale) * (weight block scale).
 // ------------------------------------------------------------------------------------
 constexpr int kMoeBN = 256, kMoeStages = 3;
-constexpr int kMoeStageA = kMoeBM * 128, kMoeStageB = kMoeBN * 128, kMoeStage = kMoeStageA + kMoeStageB;
 constexpr int kMoeMaxKB = 64;                       // 128-blocks along k: H, I <= 8192
-constexpr int kMoeSaPitch = kMoeMaxKB + 1;          // floats per row of the row-scale table (odd: no bank conflicts)
 
-template <bool UP>
+template <bool UP, int BM>
 __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
-    __shared__ __attribute__((aligned(16))) char smem[kMoeStages * kMoeStage];
-    __shared__ float sa_tab[kMoeBM * kMoeSaPitch];   // row scale of every routed row and stage
+    constexpr int kStageA = BM * 128, kStageB = kMoeBN * 128, kStage = kStageA + kStageB;
+    constexpr int NA = BM / 64;                     // copy instructions of the routed rows per wavefront and stage
+    constexpr int MB = BM / 64;                     // 32-row blocks of routed rows per wavefront
+    constexpr int RPW = BM / 8;                     // routed rows whose scale a wavefront copies per stage
+    constexpr int kCopies = NA + 4 + 1;             // vmem operations per wavefront and stage
+    constexpr int kSaBytes = 8 * 256;               // per stage: 8 wavefronts x 64 dwords (the first RPW of each are used)
+    __shared__ __attribute__((aligned(16))) char smem[kMoeStages * kStage];
+    __shared__ __attribute__((aligned(16))) float sa_stage[kMoeStages * kSaBytes / 4];
     __shared__ float sb_tab[2 * kMoeMaxKB];          // weight block scale of the tile's two 128-row blocks and every stage
 
     const int tid = threadIdx.x;
@@ -171,14 +193,19 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     const int KB = UP ? p.H : p.I;                  // bytes (= elements) per row of both operands
     const int nK = KB >> 7;
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
+    const unsigned sa_base = (unsigned)(size_t)LDS_PTR(float, sa_stage) + wave * 256;
 
-    // ---- copies: per stage this wavefront issues instruction `wave` of the 8 of the routed rows
-    // and instructions wave + 8 n (n = 0..3) of the 32 of the weights ----
-    unsigned a_off, b_off[4];
+    // ---- copies: per stage this wavefront issues instructions wave + 8 n of the routed rows (n < NA)
+    // and of the weights (n < 4), and one dword copy of the row scales of rows RPW wave .. ----
+    unsigned a_off[NA], b_off[4], s_off;
     {
-        const int r = min(kt_dma_row(wave, lane), rows - 1);          // rows past the tile re-read its last row
-        const int src = UP ? p.sorted_tok[row0 + r] : row0 + r;
-        a_off = (unsigned)src * (unsigned)KB + 16u * (unsigned)kt_dma_chunk(wave, lane);
+#pragma unroll
+        for (int n = 0; n < NA; ++n) {
+            const int i = wave + 8 * n;
+            const int r = min(kt_dma_row(i, lane), rows - 1);         // rows past the tile re-read its last row
+            const int src = UP ? p.sorted_tok[row0 + r] : row0 + r;
+            a_off[n] = (unsigned)src * (unsigned)KB + 16u * (unsigned)kt_dma_chunk(i, lane);
+        }
 #pragma unroll
         for (int n = 0; n < 4; ++n) {
             const int i = wave + 8 * n, tr = kt_dma_row(i, lane);
@@ -187,31 +214,28 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
             else wrow = min(nt * kMoeBN + tr, p.H - 1);               // rows past H re-read the last one
             b_off[n] = (unsigned)wrow * (unsigned)KB + 16u * (unsigned)kt_dma_chunk(i, lane);
         }
+        const int r = min(RPW * wave + (lane % RPW), rows - 1);
+        const int src = UP ? p.sorted_tok[row0 + r] : row0 + r;
+        s_off = 4u * (unsigned)src * (unsigned)nK;
     }
     const char* const a_base = UP ? (const char*)p.xq : (const char*)p.aq;
     const char* const b_base = UP ? (const char*)(p.w13 + (size_t)e * 2 * (size_t)p.I * (size_t)p.H)
                                   : (const char*)(p.w2 + (size_t)e * (size_t)p.H * (size_t)p.I);
+    const char* const s_base = UP ? (const char*)p.xs : (const char*)p.as;
     const unsigned lds_copy_base = lds_base + wave * 1024;
     auto dma_stage = [&](int U, auto sc) __attribute__((always_inline)) {
         constexpr int s = decltype(sc)::value;
-        dma_to_lds_16B<s * kMoeStage>(a_base + (size_t)U * 128, a_off, lds_copy_base);
-        static_for<0, 4>([&](auto n) __attribute__((always_inline)) {
-            dma_to_lds_16B<s * kMoeStage + kMoeStageA + n.value * 8192>(b_base + (size_t)U * 128, b_off[n.value], lds_copy_base);
+        static_for<0, NA>([&](auto n) __attribute__((always_inline)) {
+            dma_to_lds_16B<s * kStage + n.value * 8192>(a_base + (size_t)U * 128, a_off[n.value], lds_copy_base);
         });
+        static_for<0, 4>([&](auto n) __attribute__((always_inline)) {
+            dma_to_lds_16B<s * kStage + kStageA + n.value * 8192>(b_base + (size_t)U * 128, b_off[n.value], lds_copy_base);
+        });
+        dma_to_lds_4B<s * kSaBytes>(s_base + (size_t)U * 4, s_off, sa_base);
     };
 
-    // ---- row scales of all stages into LDS ----
-    {
-        const float* const src = UP ? p.xs : p.as;
-        for (int idx = tid; idx < kMoeBM * nK; idx += 512) {
-            const int m = idx / nK, b = idx - m * nK;
-            const int r = min(m, rows - 1);
-            const int srow = UP ? p.sorted_tok[row0 + r] : row0 + r;
-            sa_tab[m * kMoeSaPitch + b] = src[(size_t)srow * nK + b];
-        }
-    }
     // ---- weight block scales of all stages into LDS (read back as wavefront-uniform broadcasts; a
-    // global load here would make the compiler wait for the copies in flight at every use) ----
+    // global load inside the loop would make the compiler wait for the copies in flight at every use) ----
     if (tid < 2 * nK) {
         const int which = tid / nK, b = tid - which * nK;
         const float* src;
@@ -227,20 +251,29 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-            a_addr[ks][q] = lds_base + kt_offset(32 * wm + (lane & 31), 4 * ks + 2 * half + q);
-            b_addr[ks][q] = lds_base + kMoeStageA + kt_offset(64 * wn + (lane & 31), 4 * ks + 2 * half + q);
+            a_addr[ks][q] = lds_base + kt_offset((BM / 2) * wm + (lane & 31), 4 * ks + 2 * half + q);
+            b_addr[ks][q] = lds_base + kStageA + kt_offset(64 * wn + (lane & 31), 4 * ks + 2 * half + q);
         }
+    // row scale of routed row m of the tile: copied by wavefront m / RPW as its dword m % RPW
+    int sa_idx[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int m = (BM / 2) * wm + 32 * mb + (lane & 31);
+        sa_idx[mb] = (m / RPW) * 64 + (m % RPW);
+    }
     auto frag = [&](unsigned addr0, unsigned addr1, int imm) __attribute__((always_inline)) -> i32x8 {
         const i32x4 lo = *LDS_PTR(i32x4, (size_t)(addr0 + imm));
         const i32x4 hi = *LDS_PTR(i32x4, (size_t)(addr1 + imm));
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
-    f32x16 acc[2];
+    f32x16 acc[2][MB];
 #pragma unroll
     for (int in = 0; in < 2; ++in)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[in][r] = 0.0f;
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[in][mb][r] = 0.0f;
 
     auto barrier = [&]() __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
@@ -254,25 +287,30 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
 
     auto step = [&](int U, auto sc) __attribute__((always_inline)) {
         constexpr int s = decltype(sc)::value;
-        // stage U has landed once at most the copies of stage U+1 (5 per wavefront) are outstanding
-        if (U + 1 < nK) __builtin_amdgcn_s_waitcnt(0x0075);    // vmcnt(5), lgkmcnt(0)
-        else __builtin_amdgcn_s_waitcnt(0x0070);               // vmcnt(0), lgkmcnt(0)
+        // stage U has landed once at most the copies of stage U+1 are outstanding
+        if (U + 1 < nK) __builtin_amdgcn_s_waitcnt(0x0070 | kCopies);   // vmcnt(kCopies), lgkmcnt(0)
+        else __builtin_amdgcn_s_waitcnt(0x0070);                         // vmcnt(0), lgkmcnt(0)
         asm volatile("" ::: "memory");
         barrier();                                             // stage U visible; stage U-1's buffer is free
         if (U + 2 < nK) dma_stage(U + 2, IntC<(s + 2) % kMoeStages>{});
-        const float sa = sa_tab[(32 * wm + (lane & 31)) * kMoeSaPitch + U];
         const float sb0 = sb_tab[sb_sel0 * kMoeMaxKB + U], sb1 = sb_tab[sb_sel1 * kMoeMaxKB + U];
-        const i32x8 fa0 = frag(a_addr[0][0], a_addr[0][1], s * kMoeStage);
-        const i32x8 fa1 = frag(a_addr[1][0], a_addr[1][1], s * kMoeStage);
         const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        i32x8 fb[2][2];
         static_for<0, 2>([&](auto in) __attribute__((always_inline)) {
-            const i32x8 fb0 = frag(b_addr[0][0], b_addr[0][1], s * kMoeStage + in.value * 4096);
-            const i32x8 fb1 = frag(b_addr[1][0], b_addr[1][1], s * kMoeStage + in.value * 4096);
-            f32x16 part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb0, fa0, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
-            part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb1, fa1, part, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
-            const float f = sa * (in.value == 0 ? sb0 : sb1);
+            fb[in.value][0] = frag(b_addr[0][0], b_addr[0][1], s * kStage + in.value * 4096);
+            fb[in.value][1] = frag(b_addr[1][0], b_addr[1][1], s * kStage + in.value * 4096);
+        });
+        static_for<0, MB>([&](auto mb) __attribute__((always_inline)) {
+            const float sa = sa_stage[s * (kSaBytes / 4) + sa_idx[mb.value]];
+            const i32x8 fa0 = frag(a_addr[0][0], a_addr[0][1], s * kStage + mb.value * 4096);
+            const i32x8 fa1 = frag(a_addr[1][0], a_addr[1][1], s * kStage + mb.value * 4096);
+            static_for<0, 2>([&](auto in) __attribute__((always_inline)) {
+                f32x16 part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[in.value][0], fa0, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[in.value][1], fa1, part, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                const float f = sa * (in.value == 0 ? sb0 : sb1);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[in.value][r] = fmaf(part[r], f, acc[in.value][r]);
+                for (int r = 0; r < 16; ++r) acc[in.value][mb.value][r] = fmaf(part[r], f, acc[in.value][mb.value][r]);
+            });
         });
     };
     for (int U = 0;;) {
@@ -281,53 +319,65 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
         step(U, IntC<2>{}); if (++U >= nK) break;
     }
 
-    // result layout of a lane: register r of operand `in` is weight row 32 in + 8 (r/4) + 4 half + r%4
-    // of the wavefront's 64, routed row 32 wm + lane%32
-    const int m = 32 * wm + (lane & 31);
+    // result layout of a lane: register r of operand `in`, block mb is weight row 32 in + 8 (r/4) + 4 half + r%4
+    // of the wavefront's 64, routed row (BM/2) wm + 32 mb + lane%32
     if constexpr (UP) {
         // SiLU gate, then quant128 over the tile's 128 columns of each routed row
-        float h[16];
-        float amax = 0.0f;
+        float h[MB][16], amax[MB];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float g = acc[0][r];
-            h[r] = g / (1.0f + __expf(-g)) * acc[1][r];
-            amax = fmaxf(amax, fabsf(h[r]));
-        }
-        {   // across the two halves of the wavefront (rows 4 half + ..)
-            const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
+        for (int mb = 0; mb < MB; ++mb) {
+            amax[mb] = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float g = acc[0][mb][r];
+                h[mb][r] = g / (1.0f + __expf(-g)) * acc[1][mb][r];
+                amax[mb] = fmaxf(amax[mb], fabsf(h[mb][r]));
+            }
+            // across the two halves of the wavefront (rows 4 half + ..)
+            const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(amax[mb]), __float_as_uint(amax[mb]), false, false);
             const unsigned s0 = sw[0], s1 = sw[1];
-            amax = fmaxf(__uint_as_float(s0), __uint_as_float(s1));
+            amax[mb] = fmaxf(__uint_as_float(s0), __uint_as_float(s1));
         }
         __builtin_amdgcn_s_waitcnt(0xC07F);
         barrier();                                             // every wavefront is done with the stage buffers
-        float* const ex = (float*)smem;                        // [wm][wn][32]
-        if (half == 0) ex[(wm * 4 + wn) * 32 + (lane & 31)] = amax;
+        float* const ex = (float*)smem;                        // [wm][mb][wn][32]
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            if (half == 0) ex[((wm * MB + mb) * 4 + wn) * 32 + (lane & 31)] = amax[mb];
         __builtin_amdgcn_s_waitcnt(0xC07F);
         barrier();
 #pragma unroll
-        for (int w = 0; w < 4; ++w) amax = fmaxf(amax, ex[(wm * 4 + w) * 32 + (lane & 31)]);
-        const float scale = quant_scale(amax);
-        const float inv = 1.0f / scale;
-        if (m < rows) {
-            uint8_t* const dst = p.aq + (size_t)(row0 + m) * p.I + nt * 128 + 32 * wn + 4 * half;
+        for (int mb = 0; mb < MB; ++mb) {
+            float am = amax[mb];
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4)
-                *(unsigned*)(dst + 8 * g4) = quant_pack4(h[4 * g4], h[4 * g4 + 1], h[4 * g4 + 2], h[4 * g4 + 3], inv);
-            if (wn == 0 && half == 0) p.as[(size_t)(row0 + m) * (p.I >> 7) + nt] = scale;
+            for (int w = 0; w < 4; ++w) am = fmaxf(am, ex[((wm * MB + mb) * 4 + w) * 32 + (lane & 31)]);
+            const float scale = quant_scale(am);
+            const float inv = 1.0f / scale;
+            const int m = (BM / 2) * wm + 32 * mb + (lane & 31);
+            if (m < rows) {
+                uint8_t* const dst = p.aq + (size_t)(row0 + m) * p.I + nt * 128 + 32 * wn + 4 * half;
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4)
+                    *(unsigned*)(dst + 8 * g4) = quant_pack4(h[mb][4 * g4], h[mb][4 * g4 + 1], h[mb][4 * g4 + 2], h[mb][4 * g4 + 3], inv);
+                if (wn == 0 && half == 0) p.as[(size_t)(row0 + m) * (p.I >> 7) + nt] = scale;
+            }
         }
     } else {
-        if (m < rows) {
 #pragma unroll
-            for (int in = 0; in < 2; ++in)
+        for (int mb = 0; mb < MB; ++mb) {
+            const int m = (BM / 2) * wm + 32 * mb + (lane & 31);
+            if (m < rows) {
 #pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const int c = nt * kMoeBN + 64 * wn + 32 * in + 8 * g4 + 4 * half;
-                    if (c < p.H) {
-                        const f32x4 v = {acc[in][4 * g4], acc[in][4 * g4 + 1], acc[in][4 * g4 + 2], acc[in][4 * g4 + 3]};
-                        *(f32x4*)(p.o + (size_t)(row0 + m) * p.H + c) = v;
+                for (int in = 0; in < 2; ++in)
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        const int c = nt * kMoeBN + 64 * wn + 32 * in + 8 * g4 + 4 * half;
+                        if (c < p.H) {
+                            const f32x4 v = {acc[in][mb][4 * g4], acc[in][mb][4 * g4 + 1], acc[in][mb][4 * g4 + 2], acc[in][mb][4 * g4 + 3]};
+                            *(f32x4*)(p.o + (size_t)(row0 + m) * p.H + c) = v;
+                        }
                     }
-                }
+            }
         }
     }
 }
@@ -360,11 +410,18 @@ __global__ __launch_bounds__(256) void moe_combine(MoeParams p) {
 
 int moe_launch(const MoeParams& p, int first, int last, hipStream_t stream) {
     auto on = [&](int stage) { return first <= stage && stage <= last; };
-    if (on(0)) hipLaunchKernelGGL(moe_route, dim3(1), dim3(1024), 0, stream, p);
     const long long groups = (long long)p.T * (p.H / 128);
-    if (on(1)) hipLaunchKernelGGL(moe_quant_x, dim3((unsigned)((groups + 7) / 8)), dim3(256), 0, stream, p);
-    if (on(2)) hipLaunchKernelGGL((moe_gemm<true>), dim3((unsigned)(p.max_tiles * (p.I / 128))), dim3(512), 0, stream, p);
-    if (on(3)) hipLaunchKernelGGL((moe_gemm<false>), dim3((unsigned)(p.max_tiles * ((p.H + kMoeBN - 1) / kMoeBN))), dim3(512), 0, stream, p);
+    if (on(0) || on(1))
+        hipLaunchKernelGGL(moe_prepare, dim3(1 + (on(1) ? (unsigned)((groups + 31) / 32) : 0u)), dim3(1024), 0, stream, p,
+                           (on(0) ? 1 : 0) | (on(1) ? 2 : 0));
+    const dim3 g_up((unsigned)(p.max_tiles * (p.I / 128))), g_dn((unsigned)(p.max_tiles * ((p.H + kMoeBN - 1) / kMoeBN)));
+    if (p.bm == 128) {
+        if (on(2)) hipLaunchKernelGGL((moe_gemm<true, 128>), g_up, dim3(512), 0, stream, p);
+        if (on(3)) hipLaunchKernelGGL((moe_gemm<false, 128>), g_dn, dim3(512), 0, stream, p);
+    } else {
+        if (on(2)) hipLaunchKernelGGL((moe_gemm<true, 64>), g_up, dim3(512), 0, stream, p);
+        if (on(3)) hipLaunchKernelGGL((moe_gemm<false, 64>), g_dn, dim3(512), 0, stream, p);
+    }
     if (on(4)) hipLaunchKernelGGL(moe_combine, dim3((unsigned)(((p.H / 8 + 255) / 256) * p.T)), dim3(256), 0, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }

@@ -5,21 +5,22 @@
 #include <stddef.h>
 #include <stdint.h>
 
-constexpr int kMoeBM = 64;   // rows (routed token slots of one expert) per tile of the grouped products
+constexpr int kMoeBM = 64;   // smallest row tile (routed token slots of one expert) of the grouped products: sizes the tile tables
 
 struct MoeParams {
     const __bf16* x; const int* ids; const float* wts;
     const uint8_t* w13; const float* s13; const uint8_t* w2; const float* s2;
     __bf16* y;
     int T, H, I, E, KTOP;
-    int max_tiles;            // upper bound on the number of row tiles: ceil(T*KTOP / kMoeBM) + E
+    int bm;                   // rows per tile for this call: 64 or 128
+    int max_tiles;            // upper bound on the number of row tiles: ceil(T*KTOP / bm) + E
     // workspace carve-up (all device pointers into the caller's workspace)
     int* offsets;             // [E + 1] first sorted row of each expert
     int* cursor;              // [E]     scatter cursors
     int* ntiles;              // [1]     row tiles in use
     int* tile_expert;         // [max_tiles]
     int* tile_row0;           // [max_tiles] first sorted row of the tile
-    int* tile_rows;           // [max_tiles] rows in the tile (1..kMoeBM)
+    int* tile_rows;           // [max_tiles] rows in the tile (1..bm)
     int* sorted_tok;          // [T*KTOP] token of each sorted row
     int* pos;                 // [T*KTOP] sorted row of slot (t, k), or -1 if the slot is not local
     uint8_t* xq; float* xs;   // [T, H] codes, [T, H/128] scales

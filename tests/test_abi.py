@@ -148,7 +148,7 @@ def test_moe_header_symbols_are_exported(lib):
     src = re.sub(r"/\*.*?\*/", "", open(MOE_HEADER).read(), flags=re.S)
     names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", src)
     assert set(names) == {"moe_ffn_fp8", "moe_ffn_fp8_workspace_bytes", "moe_ffn_fp8_workspace_offset", "moe_ffn_fp8_flops_per_pair",
-                          "moe_ffn_fp8_stages"}
+                          "moe_ffn_fp8_ex"}
     for name in names:
         assert hasattr(lib, name), name
     assert lib.moe_ffn_fp8_flops_per_pair(7168, 2048) == 6.0 * 7168 * 2048
@@ -172,5 +172,5 @@ def test_moe_workspace_size_and_argument_errors(lib):
     for kw in (dict(T=0), dict(H=100), dict(I=0), dict(E=0), dict(E=257), dict(K=17), dict(H=8192 + 128), dict(wsb=1024)):
         assert m(**kw) == -2, kw
     assert m(x=A16 + 2) == -4 and m(ws=A16 + 16) == -4 and m(ids=A16 + 1) == -4
-    stages = lambda a, b: lib.moe_ffn_fp8_stages(A16, A16, A16, A16, A16, A16, A16, A16, 64, 256, 128, 4, 2, A16, 1 << 30, a, b, None)
-    assert stages(-1, 4) == -3 and stages(0, 5) == -3 and stages(3, 2) == -3
+    ex = lambda a, b, rt=0: lib.moe_ffn_fp8_ex(A16, A16, A16, A16, A16, A16, A16, A16, 64, 256, 128, 4, 2, A16, 1 << 30, a, b, rt, None)
+    assert ex(-1, 4) == -3 and ex(0, 5) == -3 and ex(3, 2) == -3 and ex(0, 4, 32) == -3 and ex(0, 4, 256) == -3

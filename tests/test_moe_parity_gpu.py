@@ -40,7 +40,7 @@ VALS = I.e4m3_values()
 POS = VALS[:127]
 
 
-def run(d):
+def run(d, row_tile=0):
     import torch
     from paper_2604_18616_amd import binding
     t = {"x": torch.from_numpy(d["x"].view(np.int16)).view(torch.bfloat16).cuda()}
@@ -52,7 +52,7 @@ def run(d):
     y = torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda")
     need = binding.moe_workspace_bytes(T, H, Isz, E, K)
     ws = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda")        # garbage: nothing may rely on zeros
-    binding.moe_ffn_fp8(t["x"], t["ids"], t["wts"], t["w13"], t["s13"], t["w2"], t["s2"], y=y, workspace=ws)
+    binding.moe_ffn_fp8(t["x"], t["ids"], t["wts"], t["w13"], t["s13"], t["w2"], t["s2"], y=y, workspace=ws, row_tile=row_tile)
     torch.cuda.synchronize()
     off = lambda part: binding.moe_workspace_offset(T, H, Isz, E, K, part)
 
@@ -173,15 +173,16 @@ SMALL = [dict(T=12), dict(T=64, EP=1), dict(T=200, H=384, I=256, E=3, KTOP=3, EP
          dict(T=300, H=512, I=384, E=8, KTOP=4, EP=2), dict(T=1, H=256, I=128, E=4, KTOP=2, EP=1), dict(T=9, EP=16)]
 
 
+@pytest.mark.parametrize("row_tile", [64, 128])
 @pytest.mark.parametrize("cfg", SMALL)
-def test_small_configurations(cfg):
+def test_small_configurations(cfg, row_tile):
     c = dict(H=256, I=128, E=4, KTOP=2, EP=2)
     c.update(cfg)
     T = c.pop("T")
     w = I.MoeWorkload("t", T, 40 + T, **c)
     d = I.make_moe(w)
-    print("moe case", w, "local slots", w.local_slots(d["ids"]), flush=True)
-    g = run(d)
+    print("moe case", w, "local slots", w.local_slots(d["ids"]), "row tile", row_tile, flush=True)
+    g = run(d, row_tile)
     check_routing(w, d, g)
     tokens = list(range(min(T, 24))) + ([T - 1] if T > 24 else [])
     check_stage1(w, d, g, tokens)
@@ -189,11 +190,12 @@ def test_small_configurations(cfg):
     sanity_net(g["y"], oracle.moe_ref(**d), str(w))
 
 
-def test_many_rows_per_expert_span_several_row_tiles():
-    w = I.MoeWorkload("t", 700, 77, H=256, I=256, E=2, KTOP=2, EP=1)      # 700 rows per expert: 11 tiles of 64, ragged last
+@pytest.mark.parametrize("row_tile", [64, 128])
+def test_many_rows_per_expert_span_several_row_tiles(row_tile):
+    w = I.MoeWorkload("t", 700, 77, H=256, I=256, E=2, KTOP=2, EP=1)      # 700 rows per expert: 11 tiles of 64 / 6 of 128, ragged last
     d = I.make_moe(w)
-    print("moe case", w, flush=True)
-    g = run(d)
+    print("moe case", w, "row tile", row_tile, flush=True)
+    g = run(d, row_tile)
     check_routing(w, d, g)
     tokens = [0, 1, 63, 64, 65, 350, 639, 640, 698, 699]
     check_stage1(w, d, g, tokens)
@@ -209,11 +211,12 @@ def test_no_local_expert_at_all():
     assert not g["y"].any() and int(g["offsets"][w.E]) == 0 and np.all(g["pos"] == -1)
 
 
-def test_paper_shape_on_sampled_tokens():
+@pytest.mark.parametrize("row_tile", [0, 128])
+def test_paper_shape_on_sampled_tokens(row_tile):
     w = I.MOE_WORKLOADS["M1024"]
     d = I.make_moe(w)
-    print("moe workload", w, "local slots", w.local_slots(d["ids"]), flush=True)
-    g = run(d)
+    print("moe workload", w, "local slots", w.local_slots(d["ids"]), "row tile", row_tile, flush=True)
+    g = run(d, row_tile)
     check_routing(w, d, g)
     tokens = I.sample_tokens(w, d["ids"], 12).tolist()
     check_stage1(w, d, g, tokens)

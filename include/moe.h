@@ -78,6 +78,7 @@ int moe_ffn_fp8_ex(const void *x, const int *ids, const float *wts,
  *   0 offsets    int32 [E+1]      first row of each expert (offsets[E] = number of local slots)
  *   6 sorted_tok int32 [T*KTOP]   token of each row            7 pos  int32 [T*KTOP]  row of slot (t,k) or -1
  *   8 xq         e4m3  [T, H]     quantized activations        9 xs   fp32 [T, H/128] their scales
+ *                (both only for tokens that have a local slot)
  *  10 aq         e4m3  [rows, I]  quantized intermediate      11 as   fp32 [rows, I/128]
  *  12 o          fp32  [rows, H]  down-projection rows
  * (1-5 are internal scheduling tables.)  Host only.

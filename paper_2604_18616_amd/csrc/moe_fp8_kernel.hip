@@ -73,45 +73,58 @@ __device__ __forceinline__ unsigned quant_pack4(float v0, float v1, float v2, fl
 }
 
 // ------------------------------------------------------------------------------------
-// Routing: one workgroup.  Rows within an expert are in arrival order of the atomics: every
-// row is computed independently and found again through `pos`, so the order does not show.
+// Routing: one workgroup of 16 wavefronts.  Thousands of slots land on a few dozen counters, so each
+// wavefront counts into a histogram of its own (LDS atomics without a return value); the per-expert
+// totals and the wavefronts' shares are turned into start rows by a block-wide scan; the scatter
+// pass takes its row from the wavefront's own counter again, so only lanes of one wavefront ever
+// contend.  Rows within an expert come out in no particular order: every row is computed on its
+// own and found again through `pos`.
 // ------------------------------------------------------------------------------------
 __device__ __forceinline__ void route_block(const MoeParams& p) {
-    __shared__ int cnt[256], start[257], tstart[257], cur[256];
-    const int tid = threadIdx.x, E = p.E, n = p.T * p.KTOP;
-    for (int e = tid; e < 256; e += 1024) cnt[e] = 0;
+    __shared__ int wcnt[16 * 256];          // [wavefront][expert]: counts, then running row cursors
+    __shared__ int rows_scan[256], tiles_scan[256], cnt[256];
+    const int tid = threadIdx.x, wave = tid >> 6, E = p.E, n = p.T * p.KTOP;
+    for (int i = tid; i < 16 * 256; i += 1024) wcnt[i] = 0;
     __syncthreads();
     for (int i = tid; i < n; i += 1024) {
         const int e = p.ids[i];
-        if (e >= 0 && e < E) atomicAdd(&cnt[e], 1);
+        if (e >= 0 && e < E) atomicAdd(&wcnt[wave * 256 + e], 1);
     }
     __syncthreads();
-    if (tid == 0) {
-        int rows = 0, tiles = 0;
-        for (int e = 0; e < E; ++e) {
-            start[e] = rows; tstart[e] = tiles;
-            rows += cnt[e]; tiles += (cnt[e] + p.bm - 1) / p.bm;
-        }
-        start[E] = rows; tstart[E] = tiles;
-        p.ntiles[0] = tiles;
+    if (tid < 256) {                         // expert tid: total, and each wavefront's offset inside the expert
+        int run = 0;
+        if (tid < E)
+            for (int w = 0; w < 16; ++w) { const int c = wcnt[w * 256 + tid]; wcnt[w * 256 + tid] = run; run += c; }
+        cnt[tid] = run;
+        rows_scan[tid] = run;
+        tiles_scan[tid] = (run + p.bm - 1) / p.bm;
     }
     __syncthreads();
-    for (int e = tid; e <= E; e += 1024) p.offsets[e] = start[e];
-    for (int e = tid; e < E; e += 1024) {
-        cur[e] = start[e];
-        const int nt = tstart[e + 1] - tstart[e];
+    for (int d = 1; d < 256; d <<= 1) {      // inclusive scans over the experts
+        int r = 0, t = 0;
+        if (tid < 256 && tid >= d) { r = rows_scan[tid - d]; t = tiles_scan[tid - d]; }
+        __syncthreads();
+        if (tid < 256) { rows_scan[tid] += r; tiles_scan[tid] += t; }
+        __syncthreads();
+    }
+    if (tid < E) {
+        const int start = rows_scan[tid] - cnt[tid], tstart = tiles_scan[tid] - (cnt[tid] + p.bm - 1) / p.bm;
+        p.offsets[tid] = start;
+        for (int w = 0; w < 16; ++w) wcnt[w * 256 + tid] += start;
+        const int nt = (cnt[tid] + p.bm - 1) / p.bm;
         for (int m = 0; m < nt; ++m) {
-            p.tile_expert[tstart[e] + m] = e;
-            p.tile_row0[tstart[e] + m] = start[e] + m * p.bm;
-            p.tile_rows[tstart[e] + m] = min(p.bm, cnt[e] - m * p.bm);
+            p.tile_expert[tstart + m] = tid;
+            p.tile_row0[tstart + m] = start + m * p.bm;
+            p.tile_rows[tstart + m] = min(p.bm, cnt[tid] - m * p.bm);
         }
+        if (tid == E - 1) { p.offsets[E] = rows_scan[tid]; p.ntiles[0] = tiles_scan[tid]; }
     }
     __syncthreads();
     for (int i = tid; i < n; i += 1024) {
         const int e = p.ids[i];
         int r = -1;
         if (e >= 0 && e < E) {
-            r = atomicAdd(&cur[e], 1);
+            r = atomicAdd(&wcnt[wave * 256 + e], 1);
             p.sorted_tok[r] = i / p.KTOP;
         }
         p.pos[i] = r;
@@ -122,20 +135,36 @@ __device__ __forceinline__ void route_block(const MoeParams& p) {
 // Activation quantization: 32 lanes per group of 128 features, 4 features per lane.
 // ------------------------------------------------------------------------------------
 __device__ __forceinline__ void quant_x_block(const MoeParams& p, unsigned block) {
-    const long long g = (long long)block * 32 + (threadIdx.x >> 5);
-    const long long groups = (long long)p.T * (p.H / 128);
-    if (g >= groups) return;
+    // 32 lanes take kQG consecutive groups of one token (all loads issued before the first use)
+    constexpr int kQG = 4;
+    const int gpt = p.H / 128;                                    // groups per token
+    const int cpt = (gpt + kQG - 1) / kQG;                        // 32-lane work items per token
+    const long long item = (long long)block * 32 + (threadIdx.x >> 5);
+    if (item >= (long long)p.T * cpt) return;
+    const int t = (int)(item / cpt), g0 = (int)(item - (long long)t * cpt) * kQG;
+    {   // tokens without a local slot are never read by the products: skip them
+        bool local = false;
+        for (int k = 0; k < p.KTOP; ++k) { const int e = p.ids[t * p.KTOP + k]; local |= (e >= 0 && e < p.E); }
+        if (!local) return;
+    }
     const int l = threadIdx.x & 31;
-    const u32x2 raw = *(const u32x2*)(p.x + g * 128 + l * 4);
-    const float v0 = __uint_as_float(raw[0] << 16), v1 = __uint_as_float(raw[0] & 0xffff0000u);
-    const float v2 = __uint_as_float(raw[1] << 16), v3 = __uint_as_float(raw[1] & 0xffff0000u);
-    float amax = fmaxf(fmaxf(fabsf(v0), fabsf(v1)), fmaxf(fabsf(v2), fabsf(v3)));
+    u32x2 raw[kQG];
 #pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 32));
-    const float scale = quant_scale(amax);
-    const float inv = 1.0f / scale;
-    *(unsigned*)(p.xq + g * 128 + l * 4) = quant_pack4(v0, v1, v2, v3, inv);
-    if (l == 0) p.xs[g] = scale;
+    for (int q = 0; q < kQG; ++q) raw[q] = *(const u32x2*)(p.x + ((size_t)t * gpt + min(g0 + q, gpt - 1)) * 128 + l * 4);
+#pragma unroll
+    for (int q = 0; q < kQG; ++q) {
+        if (g0 + q >= gpt) break;
+        const size_t g = (size_t)t * gpt + g0 + q;
+        const float v0 = __uint_as_float(raw[q][0] << 16), v1 = __uint_as_float(raw[q][0] & 0xffff0000u);
+        const float v2 = __uint_as_float(raw[q][1] << 16), v3 = __uint_as_float(raw[q][1] & 0xffff0000u);
+        float amax = fmaxf(fmaxf(fabsf(v0), fabsf(v1)), fmaxf(fabsf(v2), fabsf(v3)));
+#pragma unroll
+        for (int off = 16; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 32));
+        const float scale = quant_scale(amax);
+        const float inv = 1.0f / scale;
+        *(unsigned*)(p.xq + g * 128 + l * 4) = quant_pack4(v0, v1, v2, v3, inv);
+        if (l == 0) p.xs[g] = scale;
+    }
 }
 
 // Stages 0 and 1 do not depend on each other: one launch, workgroup 0 routes while the others quantize.
@@ -410,9 +439,9 @@ __global__ __launch_bounds__(256) void moe_combine(MoeParams p) {
 
 int moe_launch(const MoeParams& p, int first, int last, hipStream_t stream) {
     auto on = [&](int stage) { return first <= stage && stage <= last; };
-    const long long groups = (long long)p.T * (p.H / 128);
+    const long long items = (long long)p.T * ((p.H / 128 + 3) / 4);   // quantization: 4 groups of a token per 32 lanes
     if (on(0) || on(1))
-        hipLaunchKernelGGL(moe_prepare, dim3(1 + (on(1) ? (unsigned)((groups + 31) / 32) : 0u)), dim3(1024), 0, stream, p,
+        hipLaunchKernelGGL(moe_prepare, dim3(1 + (on(1) ? (unsigned)((items + 31) / 32) : 0u)), dim3(1024), 0, stream, p,
                            (on(0) ? 1 : 0) | (on(1) ? 2 : 0));
     const dim3 g_up((unsigned)(p.max_tiles * (p.I / 128))), g_dn((unsigned)(p.max_tiles * ((p.H + kMoeBN - 1) / kMoeBN)));
     if (p.bm == 128) {

@@ -19,7 +19,7 @@ Two things make an end-to-end tolerance meaningless here, so the path is checked
 
   routing   pos is a bijection of the local slots onto the rows, rows are grouped by expert in
             expert order, sorted_tok inverts pos                                  (exact)
-  stage 1   xq, xs == quant128(x)                                                 (exact)
+  stage 1   xq, xs == quant128(x) for every token that has a local slot            (exact)
   stage 2   with g, u the reference gate/up sums and dg = U(g), du = U(u), the kernel's value
             of a = silu(g) u is uncertain by da = 1.1 |u| dg + |silu(g)| du + 2e-5 |a| (fast
             exp, division); every group scale must be amax/448 within da(argmax)/448, every
@@ -96,6 +96,8 @@ def check_routing(w, d, g):
 def check_stage1(w, d, g, tokens):
     xf = I.bf16_bits_to_f32(d["x"])
     for t in tokens:
+        if not ((d["ids"][t] >= 0) & (d["ids"][t] < w.E)).any():
+            continue                                   # never read by the products: the kernel skips them
         for b in range(w.H // 128):
             code, scale = oracle.quant_group(xf[t, 128 * b:128 * b + 128])
             assert np.array_equal(g["xq"][t, 128 * b:128 * b + 128], code), ("xq", t, b)

@@ -178,7 +178,7 @@ __global__ __launch_bounds__(1024) void moe_prepare(MoeParams p, int stages) {
 }
 
 // ------------------------------------------------------------------------------------
-// Grouped block-scaled FP8 product.  Workgroup = 8 wavefronts = 4 (n) x 2 (m): 256 weight rows x
+// Grouped block-scaled FP8 product.  Workgroup = 8 wavefronts = 4 (n) x 2 (m) for the MFMAs: 256 weight rows x
 // BM routed rows (BM = 64 or 128, chosen on the host from the number of slots per expert);
 // wavefront (wn, wm): weight rows 64 wn .. +63 as two 32-row MFMA operands, routed rows
 // (BM/2) wm .. in the lanes, BM/64 blocks of 32 (transposed product, as in the bf16 GEMM).
@@ -198,7 +198,9 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     constexpr int NA = BM / 64;                     // copy instructions of the routed rows per wavefront and stage
     constexpr int MB = BM / 64;                     // 32-row blocks of routed rows per wavefront
     constexpr int RPW = BM / 8;                     // routed rows whose scale a wavefront copies per stage
-    constexpr int kCopies = NA + 4 + 1;             // vmem operations per wavefront and stage
+    constexpr int kCopies = 2 * NA + 8 + 2;         // vmem operations per copying wavefront and stage
+    // s_waitcnt immediate for vmcnt(kCopies), lgkmcnt(0): vmcnt's low four bits, then its two high bits at 14
+    constexpr int kWaitNext = 0x0070 | (kCopies & 15) | ((kCopies >> 4) << 14);
     constexpr int kSaBytes = 8 * 256;               // per stage: 8 wavefronts x 64 dwords (the first RPW of each are used)
     __shared__ __attribute__((aligned(16))) char smem[kMoeStages * kStage];
     __shared__ __attribute__((aligned(16))) float sa_stage[kMoeStages * kSaBytes / 4];
@@ -222,45 +224,55 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     const int KB = UP ? p.H : p.I;                  // bytes (= elements) per row of both operands
     const int nK = KB >> 7;
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
-    const unsigned sa_base = (unsigned)(size_t)LDS_PTR(float, sa_stage) + wave * 256;
 
-    // ---- copies: per stage this wavefront issues instructions wave + 8 n of the routed rows (n < NA)
-    // and of the weights (n < 4), and one dword copy of the row scales of rows RPW wave .. ----
-    unsigned a_off[NA], b_off[4], s_off;
+    // ---- copies: wavefronts 0-3 (one per SIMD) issue them: per stage instructions c + 4 n of the
+    // routed rows (n < 2 NA) and of the weights (n < 8), and the dword copies of the row scales for
+    // the row groups c and c + 4.  Wavefronts 4-7 issue no memory traffic in the loop: four issuers
+    // measured 5-10 % faster than eight.  (An L2 warm-up by the idle wavefronts, as in the bf16 GEMM,
+    // was tried and is harmful here: an XCD's L2 holds 128 KB per CU, less than the LDS stages
+    // already in flight, so lines touched early are evicted before the copies ask for them.) ----
+    const bool copier = wave < 4;
+    const int c4 = wave & 3;
+    unsigned a_off[2 * NA], b_off[8], s_off[2];
     {
 #pragma unroll
-        for (int n = 0; n < NA; ++n) {
-            const int i = wave + 8 * n;
+        for (int n = 0; n < 2 * NA; ++n) {
+            const int i = c4 + 4 * n;
             const int r = min(kt_dma_row(i, lane), rows - 1);         // rows past the tile re-read its last row
             const int src = UP ? p.sorted_tok[row0 + r] : row0 + r;
             a_off[n] = (unsigned)src * (unsigned)KB + 16u * (unsigned)kt_dma_chunk(i, lane);
         }
 #pragma unroll
-        for (int n = 0; n < 4; ++n) {
-            const int i = wave + 8 * n, tr = kt_dma_row(i, lane);
+        for (int n = 0; n < 8; ++n) {
+            const int i = c4 + 4 * n, tr = kt_dma_row(i, lane);
             int wrow;
             if (UP) wrow = ((tr & 63) >> 5) * p.I + nt * 128 + ((tr >> 6) << 5) + (tr & 31);
             else wrow = min(nt * kMoeBN + tr, p.H - 1);               // rows past H re-read the last one
             b_off[n] = (unsigned)wrow * (unsigned)KB + 16u * (unsigned)kt_dma_chunk(i, lane);
         }
-        const int r = min(RPW * wave + (lane % RPW), rows - 1);
-        const int src = UP ? p.sorted_tok[row0 + r] : row0 + r;
-        s_off = 4u * (unsigned)src * (unsigned)nK;
+#pragma unroll
+        for (int n = 0; n < 2; ++n) {
+            const int r = min(RPW * (c4 + 4 * n) + (lane % RPW), rows - 1);
+            const int src = UP ? p.sorted_tok[row0 + r] : row0 + r;
+            s_off[n] = 4u * (unsigned)src * (unsigned)nK;
+        }
     }
     const char* const a_base = UP ? (const char*)p.xq : (const char*)p.aq;
     const char* const b_base = UP ? (const char*)(p.w13 + (size_t)e * 2 * (size_t)p.I * (size_t)p.H)
                                   : (const char*)(p.w2 + (size_t)e * (size_t)p.H * (size_t)p.I);
     const char* const s_base = UP ? (const char*)p.xs : (const char*)p.as;
-    const unsigned lds_copy_base = lds_base + wave * 1024;
+    const unsigned lds_copy_base = lds_base + c4 * 1024;
+    const unsigned sa_base = (unsigned)(size_t)LDS_PTR(float, sa_stage) + c4 * 256;
     auto dma_stage = [&](int U, auto sc) __attribute__((always_inline)) {
         constexpr int s = decltype(sc)::value;
-        static_for<0, NA>([&](auto n) __attribute__((always_inline)) {
-            dma_to_lds_16B<s * kStage + n.value * 8192>(a_base + (size_t)U * 128, a_off[n.value], lds_copy_base);
+        static_for<0, 2 * NA>([&](auto n) __attribute__((always_inline)) {
+            dma_to_lds_16B<s * kStage + n.value * 4096>(a_base + (size_t)U * 128, a_off[n.value], lds_copy_base);
         });
-        static_for<0, 4>([&](auto n) __attribute__((always_inline)) {
-            dma_to_lds_16B<s * kStage + kStageA + n.value * 8192>(b_base + (size_t)U * 128, b_off[n.value], lds_copy_base);
+        static_for<0, 8>([&](auto n) __attribute__((always_inline)) {
+            dma_to_lds_16B<s * kStage + kStageA + n.value * 4096>(b_base + (size_t)U * 128, b_off[n.value], lds_copy_base);
         });
-        dma_to_lds_4B<s * kSaBytes>(s_base + (size_t)U * 4, s_off, sa_base);
+        dma_to_lds_4B<s * kSaBytes>(s_base + (size_t)U * 4, s_off[0], sa_base);
+        dma_to_lds_4B<s * kSaBytes + 1024>(s_base + (size_t)U * 4, s_off[1], sa_base);
     };
 
     // ---- weight block scales of all stages into LDS (read back as wavefront-uniform broadcasts; a
@@ -311,17 +323,20 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     };
 
     // ---- prologue: two stages in flight ----
-    dma_stage(0, IntC<0>{});
-    if (1 < nK) dma_stage(1, IntC<1>{});
+    if (copier) {
+        dma_stage(0, IntC<0>{});
+        if (1 < nK) dma_stage(1, IntC<1>{});
+    }
 
     auto step = [&](int U, auto sc) __attribute__((always_inline)) {
         constexpr int s = decltype(sc)::value;
         // stage U has landed once at most the copies of stage U+1 are outstanding
-        if (U + 1 < nK) __builtin_amdgcn_s_waitcnt(0x0070 | kCopies);   // vmcnt(kCopies), lgkmcnt(0)
+        if (!copier) __builtin_amdgcn_s_waitcnt(0xC07F);                 // lgkmcnt(0): nothing of its own in flight
+        else if (U + 1 < nK) __builtin_amdgcn_s_waitcnt(kWaitNext);      // vmcnt(kCopies), lgkmcnt(0)
         else __builtin_amdgcn_s_waitcnt(0x0070);                         // vmcnt(0), lgkmcnt(0)
         asm volatile("" ::: "memory");
         barrier();                                             // stage U visible; stage U-1's buffer is free
-        if (U + 2 < nK) dma_stage(U + 2, IntC<(s + 2) % kMoeStages>{});
+        if (copier && U + 2 < nK) dma_stage(U + 2, IntC<(s + 2) % kMoeStages>{});
         const float sb0 = sb_tab[sb_sel0 * kMoeMaxKB + U], sb1 = sb_tab[sb_sel1 * kMoeMaxKB + U];
         const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
         i32x8 fb[2][2];

@@ -62,7 +62,7 @@ int moe_ffn_fp8(const void *x, const int *ids, const float *wts,
  *       with SiLU and requantization, 3 down product, 4 combine); the stages before first_stage must have run
  *       on the same arguments, workspace and row_tile.  moe_ffn_fp8 is 0..4.
  *   row_tile  rows of one expert per workgroup of the two products: 64, 128, or 0 = what moe_ffn_fp8 does
- *       (128 when T*KTOP >= 1024*E, else 64).
+ *       (128 when T*KTOP >= 512*E, else 64).
  * A stage range outside 0..4 or another row_tile: ATTN_ERR_UNSUPPORTED.
  */
 int moe_ffn_fp8_ex(const void *x, const int *ids, const float *wts,

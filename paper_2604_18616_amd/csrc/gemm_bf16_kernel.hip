@@ -78,6 +78,7 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_b
     constexpr int kBM = T::BM, kBN = T::BN, kMB = T::kMB, kNB = T::kNB, kWaveM = T::kWaveM;
     constexpr int kStageA = T::kStageA, kStageB = T::kStageB, kBOffset = T::kBOffset;
     constexpr int kCopiers = T::kCopiers, kCopiesA = T::kCopiesA, kCopiesB = T::kCopiesB, RB = T::kNRowBytes;
+    constexpr int kBK = T::BK, kKS = T::kKS, NS = T::NS, RBK = T::kRBK;
     static_assert(kCopiesA == kCopiesB, "the copy schedule pairs one A with one B instruction");
     __shared__ __attribute__((aligned(16))) char smem[T::kLdsBytes + 256];   // stages, then the warm-up loads' sink
 
@@ -101,11 +102,11 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_b
 #pragma unroll
     for (int n = 0; n < kCopiesA; ++n) {
         const int i = w4 + kCopiers * n;
-        const int ra = min(m0 + kt_dma_row(i, lane), M - 1) - m0;               // rows past M re-read row M-1
-        a_off[n] = (unsigned)ra * a_rb + 16u * (unsigned)kt_dma_chunk(i, lane);
+        const int ra = min(m0 + kt_dma_row<RBK>(i, lane), M - 1) - m0;               // rows past M re-read row M-1
+        a_off[n] = (unsigned)ra * a_rb + 16u * (unsigned)kt_dma_chunk<RBK>(i, lane);
         if constexpr (B_NK) {
-            const int rb = min(n0 + kt_dma_row(i, lane), N - 1) - n0;
-            b_off[n] = (unsigned)rb * b_rb + 16u * (unsigned)kt_dma_chunk(i, lane);
+            const int rb = min(n0 + kt_dma_row<RBK>(i, lane), N - 1) - n0;
+            b_off[n] = (unsigned)rb * b_rb + 16u * (unsigned)kt_dma_chunk<RBK>(i, lane);
         } else {
             const int col = min(n0 + 8 * nt_dma_chunk<RB>(i, lane), N - 8) - n0;    // columns past N re-read the last piece
             b_off[n] = (unsigned)nt_dma_row<RB>(i, lane) * b_rb + 2u * (unsigned)col;
@@ -124,12 +125,12 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_b
         if constexpr (j < kCopiesA) {
             unsigned off = a_off[n];
             if constexpr (KTAIL)
-                if (U == nK - 1 && U * kBK + 8 * kt_dma_chunk(i, lane) >= K) off -= 16u * (unsigned)kt_dma_chunk(i, lane);
+                if (U == nK - 1 && U * kBK + 8 * kt_dma_chunk<RBK>(i, lane) >= K) off -= 16u * (unsigned)kt_dma_chunk<RBK>(i, lane);
             dma_to_lds_16B<buf * kStageA + n * kCopiers * 1024>(a_base + (size_t)U * (kBK * 2), off, lds_copy_base);
         } else if constexpr (B_NK) {
             unsigned off = b_off[n];
             if constexpr (KTAIL)
-                if (U == nK - 1 && U * kBK + 8 * kt_dma_chunk(i, lane) >= K) off -= 16u * (unsigned)kt_dma_chunk(i, lane);
+                if (U == nK - 1 && U * kBK + 8 * kt_dma_chunk<RBK>(i, lane) >= K) off -= 16u * (unsigned)kt_dma_chunk<RBK>(i, lane);
             dma_to_lds_16B<kBOffset + buf * kStageB + n * kCopiers * 1024>(b_base + (size_t)U * (kBK * 2), off, lds_copy_base);
         } else {
             unsigned off = b_off[n];
@@ -146,8 +147,8 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_b
                 for (int n = 0; n < kCopiesA; ++n) {
                     const int i = w4 + kCopiers * n;
                     const unsigned dst = i * 1024 + lane * 16;
-                    if (U * kBK + 8 * kt_dma_chunk(i, lane) >= K) *(u32x4*)(smem + buf * kStageA + dst) = u32x4{0u, 0u, 0u, 0u};
-                    const bool b_past = B_NK ? (U * kBK + 8 * kt_dma_chunk(i, lane) >= K) : (U * kBK + nt_dma_row<RB>(i, lane) >= K);
+                    if (U * kBK + 8 * kt_dma_chunk<RBK>(i, lane) >= K) *(u32x4*)(smem + buf * kStageA + dst) = u32x4{0u, 0u, 0u, 0u};
+                    const bool b_past = B_NK ? (U * kBK + 8 * kt_dma_chunk<RBK>(i, lane) >= K) : (U * kBK + nt_dma_row<RB>(i, lane) >= K);
                     if (b_past) *(u32x4*)(smem + kBOffset + buf * kStageB + dst) = u32x4{0u, 0u, 0u, 0u};
                 }
             }
@@ -158,10 +159,10 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_b
     unsigned a_addr[kKS];            // second MFMA operand (lanes = m), block jm adds jm * 32 rows
     unsigned b_addr[B_NK ? kKS : 2 * kNB];
 #pragma unroll
-    for (int ks = 0; ks < kKS; ++ks) a_addr[ks] = lds_base + kt_offset(kt_row(wm * kMB, lane), kt_chunk(ks, lane));
+    for (int ks = 0; ks < kKS; ++ks) a_addr[ks] = lds_base + kt_offset<RBK>(kt_row(wm * kMB, lane), kt_chunk(ks, lane));
     if constexpr (B_NK) {
 #pragma unroll
-        for (int ks = 0; ks < kKS; ++ks) b_addr[ks] = lds_base + kBOffset + kt_offset(kt_row(wn * kNB, lane), kt_chunk(ks, lane));
+        for (int ks = 0; ks < kKS; ++ks) b_addr[ks] = lds_base + kBOffset + kt_offset<RBK>(kt_row(wn * kNB, lane), kt_chunk(ks, lane));
     } else {
 #pragma unroll
         for (int in = 0; in < kNB; ++in)
@@ -173,11 +174,11 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_b
     auto read_frags = [&](auto bufc, auto ksc) __attribute__((always_inline)) {
         constexpr int buf = decltype(bufc)::value, ks = decltype(ksc)::value, set = ks & 1;
         static_for<0, kMB>([&](auto jm) __attribute__((always_inline)) {
-            fa[set][jm.value] = *LDS_PTR(bf16x8, (size_t)(a_addr[ks] + buf * kStageA + jm.value * 32 * 128));
+            fa[set][jm.value] = *LDS_PTR(bf16x8, (size_t)(a_addr[ks] + buf * kStageA + jm.value * 32 * RBK));
         });
         static_for<0, kNB>([&](auto in) __attribute__((always_inline)) {
             if constexpr (B_NK) {
-                fb[set][in.value] = *LDS_PTR(bf16x8, (size_t)(b_addr[ks] + buf * kStageB + in.value * 32 * 128));
+                fb[set][in.value] = *LDS_PTR(bf16x8, (size_t)(b_addr[ks] + buf * kStageB + in.value * 32 * RBK));
             } else {
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     LDS_PTR(s16x4, (size_t)(b_addr[2 * in.value] + buf * kStageB + ks * 16 * RB)));
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_b
     constexpr int kEarly = GEMM_EARLY < kCopiesA ? GEMM_EARLY : kCopiesA;                 // copy pairs (A, B) issued in the first sub-step, the rest in the second
     constexpr int kAhead = GEMM_AHEAD;                 // 0 switches the warm-up off
     const int nK_whole = KTAIL ? nK - 1 : nK;          // stages that lie wholly inside K
-    const bool warmer = kAhead > 0 && T::kWaves == 8 && (wave == 4 || wave == 5);
+    const bool warmer = kAhead > 0 && T::kWaves == 8 && NS == 2 && (wave == 4 || wave == 5);
     unsigned warm_off;
     if (wave == 4) {
         const int r = (tc.tn & 3) * 64 + lane;
@@ -254,61 +255,86 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_b
                      :: "v"(warm_off), "s"(src), "s"(lds_base + T::kLdsBytes) : "memory");
     };
 
-    // ---- prologue: stage 0 ----
+    // vmcnt(n) with lgkmcnt(0): n = copies of the stages that may still be in flight
+    constexpr auto vm = [](int n) constexpr { return 0x0070 | (n & 15) | ((n >> 4) << 14); };
+    constexpr int kPerStage = kCopiesA + kCopiesB;
+    // wait until this wavefront's copies of stage X have landed, given that stages up to `issued` have been issued
+    auto wait_stage = [&](int X, int issued) __attribute__((always_inline)) {
+        if (copier) {
+            const int later = min(issued, nK - 1) - X;              // stages issued after X
+            if (NS > 3 && later >= 2) __builtin_amdgcn_s_waitcnt(vm(2 * kPerStage));
+            else if (NS > 2 && later == 1) __builtin_amdgcn_s_waitcnt(vm(kPerStage));
+            else __builtin_amdgcn_s_waitcnt(vm(0));
+        } else {
+            __builtin_amdgcn_s_waitcnt(0xC07F);                     // lgkmcnt(0) only: warm-up loads stay in flight
+        }
+        asm volatile("" ::: "memory");
+    };
+    static_assert(NS <= 4, "wait_stage counts at most two later stages");
+
+    // ---- prologue: stages 0 .. NS-2 in flight, stage 0 landed ----
     if (copier) {
-        static_for<0, kCopiesA + kCopiesB>([&](auto j) __attribute__((always_inline)) { dma(0, IntC<0>{}, j); });
+        static_for<0, NS - 1>([&](auto st) __attribute__((always_inline)) {
+            if (st.value < nK) static_for<0, kPerStage>([&](auto j) __attribute__((always_inline)) { dma(st.value, st, j); });
+        });
     } else if (warmer) {
         static_for<1, kAhead>([&](auto u) __attribute__((always_inline)) { if (u.value < nK_whole) warm(u.value); });
     }
-    if (copier) wait_all();
+    wait_stage(0, NS - 2);
     zero_tail(0, 0);
     __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): the zeros are written
     barrier();
     read_frags(IntC<0>{}, IntC<0>{});
 
-    // one 64-deep stage held in LDS stage BUF
+    // one BK-deep stage U held in LDS stage BUF; the copies of stage U + NS - 1 go to the buffer stage U - 1 left
     auto step = [&](auto bufc, int U) __attribute__((always_inline)) {
         constexpr int BUF = decltype(bufc)::value;
-        const bool more = U + 1 < nK;
-        read_frags(bufc, IntC<1>{});
-        if (copier) {
-            if (more) static_for<0, kEarly>([&](auto j) __attribute__((always_inline)) { dma(U + 1, IntC<BUF ^ 1>{}, j); dma(U + 1, IntC<BUF ^ 1>{}, IntC<kCopiesA + j.value>{}); });
-        } else if (warmer && U + kAhead < nK_whole) {
-            warm(U + kAhead);
-        }
-        mfma_set(IntC<0>{});
-        read_frags(bufc, IntC<2>{});
-        if (copier && more) static_for<kEarly, kCopiesA>([&](auto j) __attribute__((always_inline)) { dma(U + 1, IntC<BUF ^ 1>{}, j); dma(U + 1, IntC<BUF ^ 1>{}, IntC<kCopiesA + j.value>{}); });
-        mfma_set(IntC<1>{});
-        read_frags(bufc, IntC<3>{});
-        mfma_set(IntC<0>{});
-        if (copier) {
-            wait_all();                             // own copies landed, own LDS reads returned
-        } else {
-            __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0) only: warm-up loads stay in flight
-            asm volatile("" ::: "memory");
-        }
-        if constexpr (KTAIL) {
-            if (U + 2 == nK) {                      // the stage just copied is the partial one
-                zero_tail(U + 1, BUF ^ 1);
-                __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0): the zeros are written
+        constexpr int NEXT = (BUF + 1) % NS, DST = (BUF + NS - 1) % NS;
+        const bool more = U + 1 < nK, copy = U + NS - 1 < nK;
+        static_for<0, kKS - 1>([&](auto ks) __attribute__((always_inline)) {
+            read_frags(bufc, IntC<ks.value + 1>{});
+            if constexpr (ks.value == 0) {
+                constexpr int first = kKS > 2 ? kEarly : kCopiesA;   // with two sub-steps everything goes here
+                if (copier) {
+                    if (copy) static_for<0, first>([&](auto j) __attribute__((always_inline)) {
+                        dma(U + NS - 1, IntC<DST>{}, j); dma(U + NS - 1, IntC<DST>{}, IntC<kCopiesA + j.value>{}); });
+                } else if (warmer && U + kAhead < nK_whole) {
+                    warm(U + kAhead);
+                }
             }
+            if constexpr (ks.value == 1) {
+                if (copier && copy) static_for<kEarly, kCopiesA>([&](auto j) __attribute__((always_inline)) {
+                    dma(U + NS - 1, IntC<DST>{}, j); dma(U + NS - 1, IntC<DST>{}, IntC<kCopiesA + j.value>{}); });
+            }
+            mfma_set(IntC<ks.value & 1>{});
+        });
+        if (more) {
+            wait_stage(U + 1, U + NS - 1);          // stage U+1 landed, own LDS reads returned
+            if constexpr (KTAIL) {
+                if (U + 2 == nK) {                  // the stage about to be published is the partial one
+                    zero_tail(U + 1, NEXT);
+                    __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0): the zeros are written
+                }
+            }
+            barrier();
+            read_frags(IntC<NEXT>{}, IntC<0>{});
         }
-        barrier();
-        if (more) read_frags(IntC<BUF ^ 1>{}, IntC<0>{});
-        mfma_set(IntC<1>{});
+        mfma_set(IntC<(kKS - 1) & 1>{});
     };
     for (int U = 0;;) {
-        step(IntC<0>{}, U);
-        if (++U >= nK) break;
-        step(IntC<1>{}, U);
-        if (++U >= nK) break;
+        bool done = false;
+        static_for<0, NS>([&](auto st) __attribute__((always_inline)) {
+            if (!done) { step(st, U); if (++U >= nK) done = true; }
+        });
+        if (done) break;
     }
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    barrier();                                      // every wavefront has read its last operands: the stages become the C staging area
 
     wait_all();                                     // the last warm-up loads have landed
 
     // ---- epilogue: C^T fragments -> bf16 -> this wavefront's 128 x 64 staging tile -> 16-byte stores ----
-    // (every wavefront has passed the last barrier after its last LDS read and no copy is in flight)
+    // (no copy is in flight: the last stage was awaited before it was read)
     char* const stage = smem + wave * (kWaveM * 128);
     const int half = lane >> 5;
 #pragma unroll
@@ -398,7 +424,7 @@ static void launch_tiled(GemmParams p, int b_is_nk, hipStream_t stream) {
     p.tiles_m = (p.M + T::BM - 1) / T::BM;
     p.tiles_n = (p.N + T::BN - 1) / T::BN;
     const dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(T::kWaves * 64);
-    const bool ktail = (p.K % kBK) != 0;
+    const bool ktail = (p.K % T::BK) != 0;
 #define GEMM_LAUNCH_TILED(NK, KT) hipLaunchKernelGGL((gemm_bf16_tiled<T, NK, KT>), grid, block, 0, stream, p)
     if (b_is_nk) { if (ktail) GEMM_LAUNCH_TILED(true, true); else GEMM_LAUNCH_TILED(true, false); }
     else         { if (ktail) GEMM_LAUNCH_TILED(false, true); else GEMM_LAUNCH_TILED(false, false); }
@@ -410,7 +436,8 @@ static void launch_tiled(GemmParams p, int b_is_nk, hipStream_t stream) {
 int gemm_launch(GemmParams p, int b_is_nk, bool tiled, int tile, hipStream_t stream) {
     if (tiled) {
         const long long large_tiles = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256);
-        if (tile == 256 || (tile == 0 && large_tiles >= 192)) launch_tiled<TileLarge>(p, b_is_nk, stream);
+        if (tile == 2564) launch_tiled<TileLarge4>(p, b_is_nk, stream);
+        else if (tile == 256 || (tile == 0 && large_tiles >= 192)) launch_tiled<TileLarge>(p, b_is_nk, stream);
         else launch_tiled<TileSmall>(p, b_is_nk, stream);
     } else {
         p.tiles_m = (p.M + 63) / 64;

@@ -15,48 +15,51 @@
 
 namespace gemm_layout {
 
-constexpr int kBK = 64, kKS = kBK / 16;         // k depth of a stage, MFMA sub-steps per stage
-constexpr int kStages = 2;
 constexpr int kWaveN = 64;                      // every wavefront tile is 64 wide in n (C staging rows of 128 bytes)
 
-// Workgroup tile BM x BN computed by WM x WN wavefronts.
-//   Tile<256, 256, 2, 4>: the large-problem shape (wavefront tile 128 x 64, one workgroup per CU);
-//   Tile<128, 128, 2, 2>: four times the workgroups for problems that would leave CUs idle
-//                         (wavefront tile 64 x 64, two workgroups per CU).
-template <int BM_, int BN_, int WM_, int WN_>
+// Workgroup tile BM x BN computed by WM x WN wavefronts, streamed in NS LDS stages of BK along k.
+//   Tile<256, 256, 2, 4, 64, 2>: the large-problem shape (wavefront tile 128 x 64, one workgroup per CU);
+//   Tile<256, 256, 2, 4, 32, 4>: the same tile in four half-depth stages (three copies in flight);
+//   Tile<128, 128, 2, 2, 64, 2>: four times the workgroups for problems that would leave CUs idle
+//                                (wavefront tile 64 x 64, two workgroups per CU).
+template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_>
 struct Tile {
-    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
+    static constexpr int kKS = BK / 16;                                     // MFMA sub-steps per stage
+    static constexpr int kRBK = BK * 2;                                     // bytes of a k-major tile row: 128 or 64
     static constexpr int kWaves = WM * WN;
     static constexpr int kWaveM = BM / WM;
     static constexpr int kMB = kWaveM / 32, kNB = kWaveN / 32;
-    static constexpr int kStageA = BM * kBK * 2, kStageB = BN * kBK * 2;   // bytes of one operand, one stage
-    static constexpr int kBOffset = kStages * kStageA;                      // B stages follow the A stages
-    static constexpr int kLdsBytes = kStages * (kStageA + kStageB);
+    static constexpr int kStageA = BM * BK * 2, kStageB = BN * BK * 2;     // bytes of one operand, one stage
+    static constexpr int kBOffset = NS * kStageA;                           // B stages follow the A stages
+    static constexpr int kLdsBytes = NS * (kStageA + kStageB);
     static constexpr int kCopiers = kWaves < 4 ? kWaves : 4;                // copying wavefronts (one per SIMD)
-    static constexpr int kCopiesA = BM / 8 / kCopiers, kCopiesB = BN / 8 / kCopiers;   // 1 KB instructions per copier and stage
+    static constexpr int kCopiesA = kStageA / 1024 / kCopiers, kCopiesB = kStageB / 1024 / kCopiers;   // 1 KB instructions per copier and stage
     static constexpr int kNRowBytes = BN * 2;                               // row of the [k][n] tile of B stored [K,N]
-    static_assert(BN / WN == kWaveN && kWaveM % 32 == 0 && kCopiesA >= 1 && kCopiesB >= 1, "unsupported tile");
+    static_assert(BN / WN == kWaveN && kWaveM % 32 == 0 && kCopiesA >= 1 && kCopiesB >= 1 && (BK == 64 || BK == 32) && kKS % 2 == 0 && NS >= 2,
+                  "unsupported tile");
 };
-using TileLarge = Tile<256, 256, 2, 4>;
-using TileSmall = Tile<128, 128, 2, 2>;
+using TileLarge = Tile<256, 256, 2, 4, 64, 2>;
+using TileLarge4 = Tile<256, 256, 2, 4, 32, 4>;
+using TileSmall = Tile<128, 128, 2, 2, 64, 2>;
 
 GEMM_HD int mfma_k(int lane, int e) { return 8 * (lane >> 5) + e; }
 GEMM_HD int mfma_rc(int lane) { return lane & 31; }                       // operand row (n) / col (m)
 GEMM_HD int mfma_out_row(int lane, int r) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
-// ---- tiles whose rows run along k (A; B stored [N,K]): BM or BN rows x 128 bytes -----------
+// ---- tiles whose rows run along k (A; B stored [N,K]): BM or BN rows x RBK bytes (128 or 64) --
 // 16-byte chunk c of row r sits at chunk position c ^ kswz(r): 16 consecutive rows of one
 // chunk column then cover all 64 banks.
-GEMM_HD int kswz(int row) { return (row >> 1) & 7; }
-GEMM_HD int kt_offset(int row, int chunk) { return row * 128 + ((chunk ^ kswz(row)) << 4); }
+template <int RBK = 128> GEMM_HD int kswz(int row) { return RBK == 128 ? (row >> 1) & 7 : (row >> 2) & 3; }
+template <int RBK = 128> GEMM_HD int kt_offset(int row, int chunk) { return row * RBK + ((chunk ^ kswz<RBK>(row)) << 4); }
 // operand of 32-row block `blk`, reduction step ks: one 16-byte read per lane
 GEMM_HD int kt_row(int blk, int lane) { return blk * 32 + (lane & 31); }
 GEMM_HD int kt_chunk(int ks, int lane) { return 2 * ks + (lane >> 5); }
-// direct-to-LDS copy, instruction i of rows/8 per tile: lane's 16 bytes land at i*1024 + lane*16
-GEMM_HD int kt_dma_row(int i, int lane) { return 8 * i + (lane >> 3); }
-GEMM_HD int kt_dma_chunk(int i, int lane) { return (lane & 7) ^ kswz(kt_dma_row(i, lane)); }
+// direct-to-LDS copy, instruction i (1024 / RBK rows each): lane's 16 bytes land at i*1024 + lane*16
+template <int RBK = 128> GEMM_HD int kt_dma_row(int i, int lane) { return (1024 / RBK) * i + lane / (RBK / 16); }
+template <int RBK = 128> GEMM_HD int kt_dma_chunk(int i, int lane) { return (lane % (RBK / 16)) ^ kswz<RBK>(kt_dma_row<RBK>(i, lane)); }
 
-// ---- B stored [K,N]: tile of 64 k-rows x RB bytes (RB = 2 BN: 512 or 256) ----------------------
+// ---- B stored [K,N]: tile of BK k-rows x RB bytes (RB = 2 BN: 512 or 256) ----------------------
 // read with ds_read_b64_tr_b16: in a 16-lane group, lane i receives as element j the element
 // i%4 of the 8 bytes addressed by lane 4*j + i/4.  Four consecutive k rows are XORed onto
 // four different 64-byte groups of the bank line.

@@ -32,12 +32,13 @@ template <class T> static Img stage_kt() {
     constexpr int kStageBytes = T::kStageA, kBM = T::BM;
     Img t(kStageBytes);
     int written = 0;
-    for (int i = 0; i < kBM / 8; ++i)
+    constexpr int RBK = T::kRBK;
+    for (int i = 0; i < kStageBytes / 1024; ++i)
         for (int lane = 0; lane < 64; ++lane) {
-            const int row = kt_dma_row(i, lane), chunk = kt_dma_chunk(i, lane);
-            CHECK(row >= 0 && row < kBM && chunk >= 0 && chunk < 8, "bad source piece row %d chunk %d", row, chunk);
+            const int row = kt_dma_row<RBK>(i, lane), chunk = kt_dma_chunk<RBK>(i, lane);
+            CHECK(row >= 0 && row < kBM && chunk >= 0 && chunk < RBK / 16, "bad source piece row %d chunk %d", row, chunk);
             const int dst = i * 1024 + lane * 16;
-            const int want = kt_offset(row, chunk);
+            const int want = kt_offset<RBK>(row, chunk);
             CHECK(dst == want, "copy destination %d != layout offset %d", dst, want);
             for (int b = 0; b < 16; ++b) {
                 CHECK(t.row[dst + b] < 0, "LDS byte %d written twice", dst + b);
@@ -49,7 +50,7 @@ template <class T> static Img stage_kt() {
     // and its LDS destination is (w * 1024) + the assembly-time constant n * kCopiers * 1024
     std::set<int> seen;
     for (int w = 0; w < T::kCopiers; ++w) for (int n = 0; n < T::kCopiesA; ++n) seen.insert(w + T::kCopiers * n);
-    CHECK((int)seen.size() == kBM / 8 && *seen.rbegin() == kBM / 8 - 1, "copy instructions not covered once");
+    CHECK((int)seen.size() == kStageBytes / 1024 && *seen.rbegin() == kStageBytes / 1024 - 1, "copy instructions not covered once");
     CHECK(T::kLdsBytes + 256 <= 160 * 1024 && (T::kWaves == 8 || 2 * (T::kLdsBytes + 256) <= 160 * 1024), "LDS budget");
     CHECK(T::kWaves * T::kWaveM * 128 <= T::kLdsBytes, "C staging does not fit the stage buffers");
     return t;
@@ -60,10 +61,10 @@ template <class T> static Img stage_nt() {
     constexpr int kStageBytes = T::kStageB, RB = T::kNRowBytes;
     Img t(kStageBytes);
     int written = 0;
-    for (int i = 0; i < T::BN / 8; ++i)
+    for (int i = 0; i < kStageBytes / 1024; ++i)
         for (int lane = 0; lane < 64; ++lane) {
             const int row = nt_dma_row<RB>(i, lane), chunk = nt_dma_chunk<RB>(i, lane);
-            CHECK(row >= 0 && row < kBK && chunk >= 0 && chunk < RB / 16, "bad source piece row %d chunk %d", row, chunk);
+            CHECK(row >= 0 && row < T::BK && chunk >= 0 && chunk < RB / 16, "bad source piece row %d chunk %d", row, chunk);
             const int dst = i * 1024 + lane * 16;
             CHECK(dst == nt_offset<RB>(row, chunk), "copy destination %d != layout offset %d", dst, nt_offset<RB>(row, chunk));
             for (int b = 0; b < 16; ++b) {
@@ -77,6 +78,7 @@ template <class T> static Img stage_nt() {
 
 template <class T> static int check_kt_operand(bool plant_bug) {
     constexpr int kStageBytes = T::kStageA, kBM = T::BM;
+    constexpr int RBK = T::kRBK, kKS = T::kKS;
     const Img t = stage_kt<T>();
     int mism = 0;
     for (int blk = 0; blk < kBM / 32; ++blk)
@@ -84,7 +86,7 @@ template <class T> static int check_kt_operand(bool plant_bug) {
             for (int lane = 0; lane < 64; ++lane) {
                 const int row = kt_row(blk, lane), chunk = kt_chunk(ks, lane);
                 // planted bug: the read forgets the swizzle (reads through the unswizzled view)
-                const int off = plant_bug ? row * 128 + chunk * 16 : kt_offset(row, chunk);
+                const int off = plant_bug ? row * RBK + chunk * 16 : kt_offset<RBK>(row, chunk);
                 if (off < 0 || off + 16 > kStageBytes) { ++mism; continue; }
                 for (int e = 0; e < 8; ++e) {
                     const bool ok = t.row[off + 2 * e] == blk * 32 + mfma_rc(lane) && t.col[off + 2 * e] == ks * 16 + mfma_k(lane, e);
@@ -97,18 +99,20 @@ template <class T> static int check_kt_operand(bool plant_bug) {
 template <class T> static void check_kt_addressing() {
     constexpr int kStageBytes = T::kStageA > T::kStageB ? T::kStageA : T::kStageB, kBM = T::BM;
     // the kernel keeps one address per sub-step and adds block / stage offsets as immediates
+    constexpr int RBK = T::kRBK, kKS = T::kKS;
     for (int blk = 0; blk < kBM / 32; ++blk)
         for (int ks = 0; ks < kKS; ++ks)
             for (int lane = 0; lane < 64; ++lane) {
-                const int base = kt_offset(kt_row(0, lane), kt_chunk(ks, lane));
-                CHECK(kt_offset(kt_row(blk, lane), kt_chunk(ks, lane)) == base + blk * 32 * 128, "block offset is not additive");
+                const int base = kt_offset<RBK>(kt_row(0, lane), kt_chunk(ks, lane));
+                CHECK(kt_offset<RBK>(kt_row(blk, lane), kt_chunk(ks, lane)) == base + blk * 32 * RBK, "block offset is not additive");
             }
-    CHECK(kStageBytes + (T::kMB - 1) * 32 * 128 < 65536, "immediate offset of a 16-byte read exceeds 16 bits");
-    CHECK(kStageBytes + 3 * 16 * T::kNRowBytes < 65536, "immediate offset of a transposing read exceeds 16 bits");
+    CHECK((T::NS - 1) * kStageBytes + (T::kMB - 1) * 32 * RBK < 65536, "immediate offset of a 16-byte read exceeds 16 bits");
+    CHECK((T::NS - 1) * kStageBytes + (kKS - 1) * 16 * T::kNRowBytes < 65536, "immediate offset of a transposing read exceeds 16 bits");
 }
 
 template <class T> static void check_nt_operand() {
     constexpr int kStageBytes = T::kStageB, RB = T::kNRowBytes, kBN = T::BN;
+    constexpr int kKS = T::kKS;
     const Img t = stage_nt<T>();
     for (int nb = 0; nb < kBN / 32; ++nb)
         for (int ks = 0; ks < kKS; ++ks)
@@ -127,12 +131,12 @@ template <class T> static void check_nt_operand() {
 }
 
 template <class T> static void check_banks() {
-    constexpr int RB = T::kNRowBytes, kBM = T::BM, kBN = T::BN;
+    constexpr int RB = T::kNRowBytes, kBM = T::BM, kBN = T::BN, RBK = T::kRBK, kKS = T::kKS;
     for (int blk = 0; blk < kBM / 32; ++blk)
         for (int ks = 0; ks < kKS; ++ks)
             for (int g = 0; g < 4; ++g) {                       // 16 lanes x 16 bytes = one 256-byte line
                 std::set<int> slots;
-                for (int l = 16 * g; l < 16 * g + 16; ++l) slots.insert((kt_offset(kt_row(blk, l), kt_chunk(ks, l)) >> 4) & 15);
+                for (int l = 16 * g; l < 16 * g + 16; ++l) slots.insert((kt_offset<RBK>(kt_row(blk, l), kt_chunk(ks, l)) >> 4) & 15);
                 CHECK(slots.size() == 16, "16-byte read: bank conflict in lane group %d (blk %d ks %d)", g, blk, ks);
             }
     for (int nb = 0; nb < kBN / 32; ++nb)
@@ -209,6 +213,7 @@ template <class T> static void check_tile_shape() {
 
 int main() {
     check_tile_shape<TileLarge>();
+    check_tile_shape<TileLarge4>();
     check_tile_shape<TileSmall>();
     check_tile_coord();
     if (failures) { printf("%d gemm layout check(s) FAILED\n", failures); return 1; }

@@ -70,6 +70,18 @@ def time_steps(torch, step, stream, steps, warmup):
     return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
+def launch_stats(torch, step, stream, n=100):
+    """Per-launch durations (HIP events around single launches): median / min / max in ms."""
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for a, b in evs:
+        a.record(stream)
+        step()
+        b.record(stream)
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in evs)
+    return {"launches": n, "median": t[n // 2], "min": t[0], "max": t[-1]}
+
+
 def mfma_sustained_tflops(torch, lib, dev, stream):
     """What this GPU sustains on nothing but bf16 MFMAs (same stream, HIP events)."""
     sink = torch.zeros(16, dtype=torch.float32, device=dev)
@@ -103,6 +115,7 @@ def bench_gemm(args, torch, lib, binding, I, dev) -> int:
             raise RuntimeError(binding.strerror(rc))
 
     ms_per_step, kernel_ms = time_steps(torch, step, stream, args.steps, args.warmup)
+    stats = launch_stats(torch, step, stream)
     sustained = mfma_sustained_tflops(torch, lib, dev, stream)
     flops = lib.gemm_bf16_flops(w.M, w.N, w.K)
     value = flops / (ms_per_step * 1e-3) / 1e12
@@ -137,7 +150,7 @@ def bench_gemm(args, torch, lib, binding, I, dev) -> int:
         "pct_of_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": read_traffic(w.name, "gemm_bf16"),
-                     "kernel_ms": kernel_ms, "mfma_sustained_tflops": sustained,
+                     "kernel_ms": kernel_ms, "kernel_ms_single_launches": stats, "mfma_sustained_tflops": sustained,
                      "frac_of_sustained": (achieved / sustained) if sustained else None},
         "cpu_baseline": cpu,
         "parity": parity,
@@ -287,6 +300,7 @@ def main() -> int:
     # timed region: K steps, wall clock bracketed by synchronize; HIP events on the launch
     # stream give the average kernel duration used for the roofline figure
     ms_per_step, kernel_ms = time_steps(torch, step, stream, args.steps, args.warmup)
+    stats = launch_stats(torch, step, stream)
     mfma_sustained = mfma_sustained_tflops(torch, lib, dev, stream)
 
     flops = lib.attn_fwd_flops(*dims, causal)
@@ -336,7 +350,7 @@ def main() -> int:
         "effective_tflops": w.dense_flops() / (ms_per_step * 1e-3) / 1e12,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": read_traffic(w.name),
-                     "kernel_ms": kernel_ms, "mfma_sustained_tflops": mfma_sustained,
+                     "kernel_ms": kernel_ms, "kernel_ms_single_launches": stats, "mfma_sustained_tflops": mfma_sustained,
                      "frac_of_sustained": (achieved / mfma_sustained) if mfma_sustained else None},
         "cpu_baseline": cpu,
         "parity": parity,

@@ -82,6 +82,20 @@ def launch_stats(torch, step, stream, n=100):
     return {"launches": n, "median": t[n // 2], "min": t[0], "max": t[-1]}
 
 
+def vendor_time_ms(torch, fn, n=30):
+    """Average duration of fn() (a PyTorch library call) over n launches after 5 warm-up calls."""
+    for _ in range(5):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n
+
+
 def mfma_sustained_tflops(torch, lib, dev, stream):
     """What this GPU sustains on nothing but bf16 MFMAs (same stream, HIP events)."""
     sink = torch.zeros(16, dtype=torch.float32, device=dev)
@@ -121,6 +135,12 @@ def bench_gemm(args, torch, lib, binding, I, dev) -> int:
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kernel_ms * 1e-3) / 1e12
 
+    vendor = None
+    if args.vendor_context:
+        bm = b.t() if w.b_is_nk else b
+        vms = vendor_time_ms(torch, lambda: torch.matmul(a, bm))
+        vendor = {"what": "torch.matmul (the BLAS library of this PyTorch build), same inputs", "ms": vms, "tflops": flops / vms / 1e9}
+
     cpu = parity = None
     if not args.no_cpu_baseline:
         from oracle import gemm_ref_samples
@@ -154,6 +174,7 @@ def bench_gemm(args, torch, lib, binding, I, dev) -> int:
                      "frac_of_sustained": (achieved / sustained) if sustained else None},
         "cpu_baseline": cpu,
         "parity": parity,
+        "vendor_context": vendor,
         "device": {"name": prop.name, "cus": prop.multi_processor_count, "clock_mhz": getattr(prop, "clock_rate", 0) / 1e3 or None},
     }
     print(json.dumps(out))
@@ -246,6 +267,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU reference leg (profiling runs)")
+    ap.add_argument("--vendor-context", action="store_true",
+                    help="also time the library PyTorch ships for the same operation on the same inputs (torch.matmul / "
+                         "scaled_dot_product_attention): context for the reader, never part of `value`")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (scales the rocprofv3 FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -307,6 +331,14 @@ def main() -> int:
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kernel_ms * 1e-3) / 1e12
 
+    vendor = None
+    if args.vendor_context:
+        import torch.nn.functional as F
+        vms = vendor_time_ms(torch, lambda: F.scaled_dot_product_attention(q, k, v, is_causal=bool(w.causal), scale=scale,
+                                                                         enable_gqa=(w.Hq != w.Hkv)))
+        vendor = {"what": "torch scaled_dot_product_attention (the fused attention of this PyTorch build), same inputs, no LSE output",
+                  "ms": vms, "tflops": flops / vms / 1e9}
+
     # parity of the last timed launch + CPU baseline: the fp64 reference on a bounded sample
     cpu = None
     parity = None
@@ -354,6 +386,7 @@ def main() -> int:
                      "frac_of_sustained": (achieved / mfma_sustained) if mfma_sustained else None},
         "cpu_baseline": cpu,
         "parity": parity,
+        "vendor_context": vendor,
         "device": {"name": prop.name, "cus": prop.multi_processor_count, "clock_mhz": getattr(prop, "clock_rate", 0) / 1e3 or None},
     }
     print(json.dumps(out))

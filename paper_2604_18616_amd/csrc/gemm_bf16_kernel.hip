@@ -222,8 +222,8 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_b
     // not in L2 yet is missed by all of them at once and every one waits out the HBM latency, which
     // two LDS stages cannot cover.  kAhead stages early, one dword of each cache line of a stage
     // is touched so that the copy issued later finds its lines in L2.  The workgroups resident on
-    // an XCD form 8 x 4 patches of tiles (tile_coord): the 4 that share an A panel each touch a
-    // quarter of its 256 lines (wavefront 4), the 8 that share a B panel an eighth (wavefront 5),
+    // an XCD form GEMM_GM x 32/GEMM_GM patches of tiles (tile_coord): those that share an A panel each
+    // touch their share of its 256 lines (wavefront 4), those that share a B panel likewise (wavefront 5),
     // which keeps the extra L2 -> L1 traffic at a fifth of the copies'.  Loads return in order, so
     // a wavefront that also copies would meet its warm-up loads again at its next wait for the
     // copies: wavefronts 4 and 5 issue no copies and wait for memory only once, at the end.  The
@@ -239,11 +239,13 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_b
     const int nK_whole = KTAIL ? nK - 1 : nK;          // stages that lie wholly inside K
     const bool warmer = kAhead > 0 && T::kWaves == 8 && NS == 2 && (wave == 4 || wave == 5);
     unsigned warm_off;
+    constexpr int kShareA = 32 / GEMM_GM, kShareB = GEMM_GM;      // workgroups of an XCD's patch that read the same A / B panel
+    static_assert(256 / kShareA <= 64 && 256 / kShareB <= 64, "one warm-up instruction per wavefront");
     if (wave == 4) {
-        const int r = (tc.tn & 3) * 64 + lane;
+        const int r = (tc.tn % kShareA) * (256 / kShareA) + lane % (256 / kShareA);
         warm_off = (unsigned)(min(m0 + r, M - 1) - m0) * a_rb;
     } else {
-        const int r = (tc.tm & 7) * 32 + (lane & 31);
+        const int r = (tc.tm % kShareB) * (256 / kShareB) + lane % (256 / kShareB);
         if (B_NK) warm_off = (unsigned)(min(n0 + r, N - 1) - n0) * b_rb;
         else warm_off = (unsigned)(r >> 2) * b_rb + 2u * (unsigned)(min(n0 + 64 * (r & 3), N - 2) - n0);
     }

@@ -84,14 +84,17 @@ GEMM_HD int c_stage_offset(int m, int n) { return m * 128 + (((n >> 3) ^ cswz(m)
 
 // ---- workgroup id -> C tile ------------------------------------------------------------------
 // Workgroups go to the 8 XCDs round-robin and each XCD has its own L2: every XCD gets a
-// contiguous range of the logical order, and the logical order walks the tiles in bands of 8
-// tile rows, column by column, so that the ~32 workgroups resident on one XCD cover an 8 x 4
+// contiguous range of the logical order, and the logical order walks the tiles in bands of GEMM_GM (4)
+// tile rows, column by column, so that the ~32 workgroups resident on one XCD cover a 4 x 8
 // patch of C and share 12 operand panels instead of 64.
 struct TileCoord { int tm, tn; };
 GEMM_HD TileCoord tile_coord(int bid, int nblocks, int tiles_m, int tiles_n) {
     const int per_xcd = nblocks >> 3;
     const int logical = (bid < per_xcd * 8) ? (bid & 7) * per_xcd + (bid >> 3) : bid;
-    const int GM = 8;
+#ifndef GEMM_GM
+#define GEMM_GM 4
+#endif
+    const int GM = GEMM_GM;
     const int band = logical / (GM * tiles_n);
     const int first = band * GM;
     const int rows = (tiles_m - first) < GM ? (tiles_m - first) : GM;

@@ -212,13 +212,27 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     const int wn = wave & 3, wm = wave >> 2;
     const int half = lane >> 5;
 
-    // workgroup -> (row tile mt, column tile nt); XCD-aware: consecutive logical ids (the row
-    // tiles of one expert, same nt, share their weight tile) stay on one XCD and its L2
-    const int nblocks = gridDim.x, bid = blockIdx.x;
-    const int per_xcd = nblocks >> 3;
-    const int logical = (bid < per_xcd * 8) ? (bid & 7) * per_xcd + (bid >> 3) : bid;
-    const int nt = logical / p.max_tiles, mt = logical - nt * p.max_tiles;
-    if (mt >= p.ntiles[0]) return;                  // uniform: before any barrier
+    // workgroup -> (row tile mt, column tile nt).  The grid has max_tiles * NT workgroups (a multiple of
+    // 8), of which ntiles * NT are live; XCD x (= blockIdx % 8) takes the x-th eighth of the live logical
+    // ids in order, so the ~32 workgroups resident on an XCD are neighbours.  Logical order: expert by
+    // expert; inside an expert column tile by column tile, the expert's row tiles innermost: neighbours
+    // share their weight tile (same nt) or their routed rows (same mt), which the XCD's L2 then
+    // fetches once.
+    const int NT = UP ? (p.I >> 7) : (p.H + kMoeBN - 1) / kMoeBN;
+    const int live = p.ntiles[0] * NT, per_xcd = (live + 7) >> 3;
+    const int bid = blockIdx.x;
+    const int logical = (bid & 7) * per_xcd + (bid >> 3);
+    if ((bid >> 3) >= per_xcd || logical >= live) return;   // uniform: before any barrier
+    int nt, mt;
+    {
+        const int mt0 = logical / NT;               // some row tile of the expert whose block holds `logical`
+        const int ee = p.tile_expert[mt0], o0 = p.offsets[ee], o1 = p.offsets[ee + 1];
+        const int first = mt0 - (p.tile_row0[mt0] - o0) / p.bm;       // the expert's first row tile
+        const int cnt = (o1 - o0 + p.bm - 1) / p.bm;                  // and how many it has
+        const int off = logical - first * NT;                         // in [0, cnt * NT)
+        nt = off / cnt;
+        mt = first + (off - nt * cnt);
+    }
 
     const int e = p.tile_expert[mt], row0 = p.tile_row0[mt], rows = p.tile_rows[mt];
     const int KB = UP ? p.H : p.I;                  // bytes (= elements) per row of both operands
@@ -458,7 +472,8 @@ int moe_launch(const MoeParams& p, int first, int last, hipStream_t stream) {
     if (on(0) || on(1))
         hipLaunchKernelGGL(moe_prepare, dim3(1 + (on(1) ? (unsigned)((items + 31) / 32) : 0u)), dim3(1024), 0, stream, p,
                            (on(0) ? 1 : 0) | (on(1) ? 2 : 0));
-    const dim3 g_up((unsigned)(p.max_tiles * (p.I / 128))), g_dn((unsigned)(p.max_tiles * ((p.H + kMoeBN - 1) / kMoeBN)));
+    auto grid8 = [](long long n) { return dim3((unsigned)((n + 7) / 8 * 8)); };   // the tile order wants a multiple of 8
+    const dim3 g_up = grid8((long long)p.max_tiles * (p.I / 128)), g_dn = grid8((long long)p.max_tiles * ((p.H + kMoeBN - 1) / kMoeBN));
     if (p.bm == 128) {
         if (on(2)) hipLaunchKernelGGL((moe_gemm<true, 128>), g_up, dim3(512), 0, stream, p);
         if (on(3)) hipLaunchKernelGGL((moe_gemm<false, 128>), g_dn, dim3(512), 0, stream, p);

@@ -21,7 +21,10 @@ constexpr int kWaveN = 64;                      // every wavefront tile is 64 wi
 //   Tile<256, 256, 2, 4, 64, 2>: the large-problem shape (wavefront tile 128 x 64, one workgroup per CU);
 //   Tile<256, 256, 2, 4, 32, 4>: the same tile in four half-depth stages (three copies in flight);
 //   Tile<128, 128, 2, 2, 64, 2>: four times the workgroups for problems that would leave CUs idle
-//                                (wavefront tile 64 x 64, two workgroups per CU).
+//                                (wavefront tile 64 x 64, two workgroups per CU);
+//   Tile<64, 64, 2, 1, 64, 4>:   sixteen times the workgroups, two wavefronts of 32 x 64 each, four stages:
+//                                for the smallest problems, where the time is the L2 -> LDS traffic of the
+//                                busiest CU and spreading it over every CU matters more than operand reuse.
 template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
@@ -42,6 +45,7 @@ struct Tile {
 using TileLarge = Tile<256, 256, 2, 4, 64, 2>;
 using TileLarge4 = Tile<256, 256, 2, 4, 32, 4>;
 using TileSmall = Tile<128, 128, 2, 2, 64, 2>;
+using TileTiny = Tile<64, 64, 2, 1, 64, 4>;
 
 GEMM_HD int mfma_k(int lane, int e) { return 8 * (lane >> 5) + e; }
 GEMM_HD int mfma_rc(int lane) { return lane & 31; }                       // operand row (n) / col (m)
@@ -59,12 +63,13 @@ GEMM_HD int kt_chunk(int ks, int lane) { return 2 * ks + (lane >> 5); }
 template <int RBK = 128> GEMM_HD int kt_dma_row(int i, int lane) { return (1024 / RBK) * i + lane / (RBK / 16); }
 template <int RBK = 128> GEMM_HD int kt_dma_chunk(int i, int lane) { return (lane % (RBK / 16)) ^ kswz<RBK>(kt_dma_row<RBK>(i, lane)); }
 
-// ---- B stored [K,N]: tile of BK k-rows x RB bytes (RB = 2 BN: 512 or 256) ----------------------
+// ---- B stored [K,N]: tile of BK k-rows x RB bytes (RB = 2 BN: 512, 256 or 128) -----------------
 // read with ds_read_b64_tr_b16: in a 16-lane group, lane i receives as element j the element
 // i%4 of the 8 bytes addressed by lane 4*j + i/4.  Four consecutive k rows are XORed onto
-// four different 64-byte groups of the bank line.
-GEMM_HD int nswz(int krow) { return (krow & 3) << 2; }
-template <int RB> GEMM_HD int nt_offset(int krow, int chunk) { return krow * RB + ((chunk ^ nswz(krow)) << 4); }
+// four different 64-byte groups of the 256-byte bank line (128-byte rows: two rows share a bank
+// line, so rows k and k+2 take different halves of their row).
+template <int RB> GEMM_HD int nswz(int krow) { return RB >= 256 ? (krow & 3) << 2 : ((krow >> 1) & 1) << 2; }
+template <int RB> GEMM_HD int nt_offset(int krow, int chunk) { return krow * RB + ((chunk ^ nswz<RB>(krow)) << 4); }
 // address lane `lane` supplies for read x (0,1) of n-block nb (32 columns), step ks
 GEMM_HD int tr_krow(int ks, int x, int lane) { return ks * 16 + 8 * (lane >> 5) + 4 * x + ((lane & 15) >> 2); }
 GEMM_HD int tr_ncol(int nb, int lane) { return nb * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3); }
@@ -76,7 +81,7 @@ GEMM_HD int tr_src_lane(int lane, int j) { return (lane & ~15) + 4 * j + ((lane 
 GEMM_HD int tr_src_elem(int lane) { return lane & 3; }
 // copy instruction i: 1024 / RB k rows of RB bytes
 template <int RB> GEMM_HD int nt_dma_row(int i, int lane) { return (1024 / RB) * i + lane / (RB / 16); }
-template <int RB> GEMM_HD int nt_dma_chunk(int i, int lane) { return (lane % (RB / 16)) ^ nswz(nt_dma_row<RB>(i, lane)); }
+template <int RB> GEMM_HD int nt_dma_chunk(int i, int lane) { return (lane % (RB / 16)) ^ nswz<RB>(nt_dma_row<RB>(i, lane)); }
 
 // ---- C staging (epilogue): per wavefront kWaveM rows (m) x 128 bytes (64 n) ------------------
 GEMM_HD int cswz(int m) { return (m >> 1) & 7; }

@@ -215,6 +215,7 @@ int main() {
     check_tile_shape<TileLarge>();
     check_tile_shape<TileLarge4>();
     check_tile_shape<TileSmall>();
+    check_tile_shape<TileTiny>();
     check_tile_coord();
     if (failures) { printf("%d gemm layout check(s) FAILED\n", failures); return 1; }
     printf("gemm layout checks passed\n");

@@ -74,7 +74,7 @@ __device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_o
 // address and zeroed in LDS by the copying wavefront before they are published).
 // ------------------------------------------------------------------------------------
 template <class T, bool B_NK, bool KTAIL>
-__global__ __launch_bounds__(T::kWaves * 64, T::kWaves == 8 ? 1 : 2) void gemm_bf16_tiled(GemmParams p) {
+__global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) void gemm_bf16_tiled(GemmParams p) {
     constexpr int kBM = T::BM, kBN = T::BN, kMB = T::kMB, kNB = T::kNB, kWaveM = T::kWaveM;
     constexpr int kStageA = T::kStageA, kStageB = T::kStageB, kBOffset = T::kBOffset;
     constexpr int kCopiers = T::kCopiers, kCopiesA = T::kCopiesA, kCopiesB = T::kCopiesB, RB = T::kNRowBytes;
@@ -433,18 +433,23 @@ static void launch_tiled(GemmParams p, int b_is_nk, hipStream_t stream) {
 #undef GEMM_LAUNCH_TILED
 }
 
-// Tile-size choice: 256 x 256 tiles when they give at least ~3/4 of the chip's 256 CUs a
-// workgroup; else 128 x 128 tiles (four times the workgroups, two resident per CU) unless even
-// those number 160 or fewer, in which case 64 x 64 tiles spread the copies over every CU
-// (measured: 1024^3 7.2 us instead of 10.0 us, 1536^3 5 % faster, 2048^3 no difference).
+// Tile-size choice by the number of tiles against the chip's 256 CUs (measured on square problems
+// from 1024 to 4096 in steps of 256-512, both layouts of B):
+//   256 x 256 tiles number at least 128             -> those (one workgroup per CU, best operand reuse);
+//   else 128 x 128 tiles number more than 256       -> those in two stages, two workgroups per CU;
+//   else they number more than 112                  -> those in four stages: one workgroup per CU, so the
+//                                                      depth of the copy pipeline has to come from one workgroup;
+//   else                                            -> 64 x 64 tiles: the time is the L2 -> LDS traffic of the
+//                                                      busiest CU, and four times the tiles spread it out.
 int gemm_launch(GemmParams p, int b_is_nk, bool tiled, int tile, hipStream_t stream) {
     if (tiled) {
         const long long large_tiles = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256);
         const long long small_tiles = (long long)((p.M + 127) / 128) * ((p.N + 127) / 128);
-        if (tile == 0) tile = large_tiles >= 192 ? 256 : small_tiles <= 160 ? 64 : 128;
+        if (tile == 0) tile = large_tiles >= 128 ? 256 : small_tiles > 256 ? 128 : small_tiles > 112 ? 1284 : 64;
         if (tile == 2564) launch_tiled<TileLarge4>(p, b_is_nk, stream);
         else if (tile == 256) launch_tiled<TileLarge>(p, b_is_nk, stream);
         else if (tile == 64) launch_tiled<TileTiny>(p, b_is_nk, stream);
+        else if (tile == 1284) launch_tiled<TileSmall4>(p, b_is_nk, stream);
         else launch_tiled<TileSmall>(p, b_is_nk, stream);
     } else {
         p.tiles_m = (p.M + 63) / 64;

@@ -22,6 +22,8 @@ constexpr int kWaveN = 64;                      // every wavefront tile is 64 wi
 //   Tile<256, 256, 2, 4, 32, 4>: the same tile in four half-depth stages (three copies in flight);
 //   Tile<128, 128, 2, 2, 64, 2>: four times the workgroups for problems that would leave CUs idle
 //                                (wavefront tile 64 x 64, two workgroups per CU);
+//   Tile<128, 128, 2, 2, 64, 4>: the same tile in four stages (128 KB, one workgroup per CU, three stages of
+//                                copies in flight) for problems with at most one such tile per CU;
 //   Tile<64, 64, 2, 1, 64, 4>:   sixteen times the workgroups, two wavefronts of 32 x 64 each, four stages:
 //                                for the smallest problems, where the time is the L2 -> LDS traffic of the
 //                                busiest CU and spreading it over every CU matters more than operand reuse.
@@ -36,6 +38,7 @@ struct Tile {
     static constexpr int kStageA = BM * BK * 2, kStageB = BN * BK * 2;     // bytes of one operand, one stage
     static constexpr int kBOffset = NS * kStageA;                           // B stages follow the A stages
     static constexpr int kLdsBytes = NS * (kStageA + kStageB);
+    static constexpr int kPerCU = (WM * WN == 8 || kLdsBytes > 80 * 1024) ? 1 : 2;   // workgroups meant to share a CU (160 KB of LDS)
     static constexpr int kCopiers = kWaves < 4 ? kWaves : 4;                // copying wavefronts (one per SIMD)
     static constexpr int kCopiesA = kStageA / 1024 / kCopiers, kCopiesB = kStageB / 1024 / kCopiers;   // 1 KB instructions per copier and stage
     static constexpr int kNRowBytes = BN * 2;                               // row of the [k][n] tile of B stored [K,N]
@@ -46,6 +49,7 @@ using TileLarge = Tile<256, 256, 2, 4, 64, 2>;
 using TileLarge4 = Tile<256, 256, 2, 4, 32, 4>;
 using TileSmall = Tile<128, 128, 2, 2, 64, 2>;
 using TileTiny = Tile<64, 64, 2, 1, 64, 4>;
+using TileSmall4 = Tile<128, 128, 2, 2, 64, 4>;
 
 GEMM_HD int mfma_k(int lane, int e) { return 8 * (lane >> 5) + e; }
 GEMM_HD int mfma_rc(int lane) { return lane & 31; }                       // operand row (n) / col (m)

@@ -51,7 +51,7 @@ template <class T> static Img stage_kt() {
     std::set<int> seen;
     for (int w = 0; w < T::kCopiers; ++w) for (int n = 0; n < T::kCopiesA; ++n) seen.insert(w + T::kCopiers * n);
     CHECK((int)seen.size() == kStageBytes / 1024 && *seen.rbegin() == kStageBytes / 1024 - 1, "copy instructions not covered once");
-    CHECK(T::kLdsBytes + 256 <= 160 * 1024 && (T::kWaves == 8 || 2 * (T::kLdsBytes + 256) <= 160 * 1024), "LDS budget");
+    CHECK(T::kPerCU * (T::kLdsBytes + 256) <= 160 * 1024, "LDS budget");
     CHECK(T::kWaves * T::kWaveM * 128 <= T::kLdsBytes, "C staging does not fit the stage buffers");
     return t;
 }
@@ -216,6 +216,7 @@ int main() {
     check_tile_shape<TileLarge4>();
     check_tile_shape<TileSmall>();
     check_tile_shape<TileTiny>();
+    check_tile_shape<TileSmall4>();
     check_tile_coord();
     if (failures) { printf("%d gemm layout check(s) FAILED\n", failures); return 1; }
     printf("gemm layout checks passed\n");

@@ -134,7 +134,7 @@ def test_gemm_argument_errors_are_reported_without_a_gpu(lib):
     assert g(lda=1 << 31) == -2
     assert g(M=(1 << 31) - 1, N=(1 << 31) - 1, ldb=(1 << 31) - 1, ldc=(1 << 31) - 1) == -2   # too many tiles
     assert g(a=A16 + 1) == -4 and g(c=A16 + 3) == -4  # odd addresses cannot hold bf16
-    assert lib.gemm_bf16_tile(A16, A16, A16, 256, 256, 64, 64, 256, 256, 0, 96, None) == -3   # tile must be 0, 64, 128, 256 or 2564
+    assert lib.gemm_bf16_tile(A16, A16, A16, 256, 256, 64, 64, 256, 256, 0, 96, None) == -3   # tile must be 0, 64, 128, 1284, 256 or 2564
     assert lib.gemm_bf16_tile(None, A16, A16, 256, 256, 64, 64, 256, 256, 0, 128, None) == -1
 
 

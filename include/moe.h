@@ -61,8 +61,9 @@ int moe_ffn_fp8(const void *x, const int *ids, const float *wts,
  *   first_stage..last_stage  run only these stages (0 routing, 1 activation quantization, 2 gate/up product
  *       with SiLU and requantization, 3 down product, 4 combine); the stages before first_stage must have run
  *       on the same arguments, workspace and row_tile.  moe_ffn_fp8 is 0..4.
- *   row_tile  rows of one expert per workgroup of the two products: 64, 128, or 0 = what moe_ffn_fp8 does
- *       (128 when T*KTOP >= 512*E, else 64).
+ *   row_tile  rows of one expert per workgroup of the two products: 64, 128, or 0 = what moe_ffn_fp8 does (128).
+ *       An expert's rows are cut into tiles of row_tile rows and a remainder (an expert with row_tile + 1 ..
+ *       row_tile + 32 rows gets a single tile); every tile runs the 64-, 128- or 160-row code that fits its rows.
  * A stage range outside 0..4 or another row_tile: ATTN_ERR_UNSUPPORTED.
  */
 int moe_ffn_fp8_ex(const void *x, const int *ids, const float *wts,

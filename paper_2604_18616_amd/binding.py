@@ -170,7 +170,7 @@ def moe_ffn_fp8(x, ids, wts, w13, s13, w2, s2, y=None, workspace=None, stream=No
     expert or negative); wts fp32 [T,KTOP]; w13 uint8 [E,2I,H] and w2 uint8 [E,H,I] (e4m3 codes);
     s13 fp32 [E,2I/128,H/128]; s2 fp32 [E,H/128,I/128].  y (bf16 [T,H]) and the workspace (uint8, at
     least moe_workspace_bytes(...)) are allocated with torch if not given.  Enqueued on `stream`
-    (default: torch's current stream); no sync.  row_tile: 0 (by size), 64 or 128 (moe_ffn_fp8_ex)."""
+    (default: torch's current stream); no sync.  row_tile: 0 (the default, 128) or 64 (moe_ffn_fp8_ex)."""
     import torch
 
     for t in (x, ids, wts, w13, s13, w2, s2):

@@ -74,9 +74,9 @@ extern "C" int moe_ffn_fp8_ex(const void* x, const int* ids, const float* wts,
     p.w13 = (const uint8_t*)w13; p.s13 = s13; p.w2 = (const uint8_t*)w2; p.s2 = s2;
     p.y = (__bf16*)y;
     p.T = T; p.H = H; p.I = I; p.E = E; p.KTOP = KTOP;
-    // row tile: 128 when the experts would get about 64 rows or more if an eighth of the slots were local
-    // (the usual expert-parallel share), else 64; `bm_override` is for tests
-    p.bm = bm_override ? bm_override : ((long long)T * KTOP >= 512LL * E ? 128 : 64);
+    // rows of one expert per row tile: 128 (a remainder of up to 32 rows joins the tile before it, and each tile
+    // runs the 64-, 128- or 160-row code that fits the rows it really has); `bm_override` is for tests
+    p.bm = bm_override ? bm_override : 128;
     p.max_tiles = (int)(((size_t)T * KTOP + p.bm - 1) / p.bm + E);
     p.offsets = (int*)(ws + off[0]); p.cursor = (int*)(ws + off[1]); p.ntiles = (int*)(ws + off[2]);
     p.tile_expert = (int*)(ws + off[3]); p.tile_row0 = (int*)(ws + off[4]); p.tile_rows = (int*)(ws + off[5]);

@@ -72,6 +72,16 @@ __device__ __forceinline__ unsigned quant_pack4(float v0, float v1, float v2, fl
     return (unsigned)p;
 }
 
+// Row tiles of an expert with cnt rows: tiles of bm rows and a remainder.  An expert with one full tile and
+// at most 32 rows more gets a single tile of up to bm + 32 rows (one more 32-row MFMA block instead of a
+// second copy of every weight tile: 13 % on the whole call where experts have about bm rows).  With two or
+// more full tiles the remainder stays a tile of its own: measured, the short tiles then cost little (their
+// weights are L2 hits) and fill the last round of workgroups, which equal long tiles leave mostly idle.
+__device__ __forceinline__ int moe_row_tiles(int cnt, int bm) {
+    const int n = cnt / bm, r = cnt - n * bm;
+    return (n == 1 && r <= 32) ? 1 : n + (r > 0 ? 1 : 0);
+}
+
 // ------------------------------------------------------------------------------------
 // Routing: one workgroup of 16 wavefronts.  Thousands of slots land on a few dozen counters, so each
 // wavefront counts into a histogram of its own (LDS atomics without a return value); the per-expert
@@ -97,7 +107,7 @@ __device__ __forceinline__ void route_block(const MoeParams& p) {
             for (int w = 0; w < 16; ++w) { const int c = wcnt[w * 256 + tid]; wcnt[w * 256 + tid] = run; run += c; }
         cnt[tid] = run;
         rows_scan[tid] = run;
-        tiles_scan[tid] = (run + p.bm - 1) / p.bm;
+        tiles_scan[tid] = moe_row_tiles(run, p.bm);
     }
     __syncthreads();
     for (int d = 1; d < 256; d <<= 1) {      // inclusive scans over the experts
@@ -108,14 +118,14 @@ __device__ __forceinline__ void route_block(const MoeParams& p) {
         __syncthreads();
     }
     if (tid < E) {
-        const int start = rows_scan[tid] - cnt[tid], tstart = tiles_scan[tid] - (cnt[tid] + p.bm - 1) / p.bm;
+        const int nt = moe_row_tiles(cnt[tid], p.bm);
+        const int start = rows_scan[tid] - cnt[tid], tstart = tiles_scan[tid] - nt;
         p.offsets[tid] = start;
         for (int w = 0; w < 16; ++w) wcnt[w * 256 + tid] += start;
-        const int nt = (cnt[tid] + p.bm - 1) / p.bm;
         for (int m = 0; m < nt; ++m) {
             p.tile_expert[tstart + m] = tid;
             p.tile_row0[tstart + m] = start + m * p.bm;
-            p.tile_rows[tstart + m] = min(p.bm, cnt[tid] - m * p.bm);
+            p.tile_rows[tstart + m] = m == nt - 1 ? cnt[tid] - m * p.bm : p.bm;   // the last tile takes what is left: up to bm + 32 rows
         }
         if (tid == E - 1) { p.offsets[E] = rows_scan[tid]; p.ntiles[0] = tiles_scan[tid]; }
     }
@@ -179,32 +189,41 @@ __global__ __launch_bounds__(1024) void moe_prepare(MoeParams p, int stages) {
 
 // ------------------------------------------------------------------------------------
 // Grouped block-scaled FP8 product.  Workgroup = 8 wavefronts = 4 (n) x 2 (m) for the MFMAs: 256 weight rows x
-// BM routed rows (BM = 64 or 128, chosen on the host from the number of slots per expert);
-// wavefront (wn, wm): weight rows 64 wn .. +63 as two 32-row MFMA operands, routed rows
+// BM routed rows.  An expert's rows are cut into tiles of p.bm (128 unless the caller asks for 64) and a
+// remainder (moe_row_tiles: an expert with bm + 1 .. bm + 32 rows gets one tile); each workgroup picks
+// the code for BM = 64, 128 or 160 from the rows its tile really has.
+// Wavefront (wn, wm): weight rows 64 wn .. +63 as two 32-row MFMA operands, routed rows
 // (BM/2) wm .. in the lanes, BM/64 blocks of 32 (transposed product, as in the bf16 GEMM).
 //   UP:  the 256 weight rows of column tile nt are, per wavefront, 32 gate rows j and the 32 up
 //        rows I + j of the same j: both accumulators of a lane meet the same (row, j).
 //   DN:  256 consecutive rows of w2.
 // One stage = 128 bytes of k for all rows (BM x 128 routed + 32 KB weights) plus the stage's row
-// scales (one dword copy per wavefront), three stages in LDS; per stage two K = 64 MFMAs per
-// operand pair into a fresh partial, then acc += partial * (row scale) * (weight block scale).
+// scales (dword copies); three stages in LDS; per stage two K = 64 MFMAs per operand pair into a fresh
+// partial, then acc += partial * (row scale) * (weight block scale).  BM = 160: five 32-row blocks, three
+// for the wavefronts wm = 0 and two for wm = 1.
 // ------------------------------------------------------------------------------------
-constexpr int kMoeBN = 256, kMoeStages = 3;
+constexpr int kMoeBN = 256;
+constexpr int kMoeLdsBytes = 3 * (160 * 128 + kMoeBN * 128);   // the largest stage set: three stages of BM = 160
+constexpr int kMoeSaBytes = 8 * 128;                          // row scales per stage: 8 row groups x 32 dwords
 constexpr int kMoeMaxKB = 64;                       // 128-blocks along k: H, I <= 8192
 
+typedef __attribute__((address_space(3))) char* LdsChar;      // LDS pointers stay typed as such: a generic pointer would
+typedef __attribute__((address_space(3))) float* LdsFloat;    // turn the scale reads into flat loads, which count as vector memory
 template <bool UP, int BM>
-__global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
+__device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int mt, int nt, LdsChar smem, LdsFloat sa_stage, LdsFloat sb_tab) {
+    constexpr int NS = 3;                           // LDS stages
     constexpr int kStageA = BM * 128, kStageB = kMoeBN * 128, kStage = kStageA + kStageB;
-    constexpr int NA = BM / 64;                     // copy instructions of the routed rows per wavefront and stage
-    constexpr int MB = BM / 64;                     // 32-row blocks of routed rows per wavefront
-    constexpr int RPW = BM / 8;                     // routed rows whose scale a wavefront copies per stage
-    constexpr int kCopies = 2 * NA + 8 + 2;         // vmem operations per copying wavefront and stage
-    // s_waitcnt immediate for vmcnt(kCopies), lgkmcnt(0): vmcnt's low four bits, then its two high bits at 14
-    constexpr int kWaitNext = 0x0070 | (kCopies & 15) | ((kCopies >> 4) << 14);
-    constexpr int kSaBytes = 8 * 256;               // per stage: 8 wavefronts x 64 dwords (the first RPW of each are used)
-    __shared__ __attribute__((aligned(16))) char smem[kMoeStages * kStage];
-    __shared__ __attribute__((aligned(16))) float sa_stage[kMoeStages * kSaBytes / 4];
-    __shared__ float sb_tab[2 * kMoeMaxKB];          // weight block scale of the tile's two 128-row blocks and every stage
+    static_assert(NS * kStage <= kMoeLdsBytes, "stages exceed the workgroup's LDS");
+    constexpr int NCA = BM / 32;                    // copy instructions of the routed rows per copying wavefront and stage
+    constexpr int kW0 = BM == 160 ? 96 : BM / 2;    // routed rows of the wavefronts wm = 0; wm = 1 takes the rest
+    constexpr int MB = BM == 160 ? 3 : BM / 64;     // 32-row blocks of routed rows per wavefront (BM = 160: the third only for wm = 0)
+    constexpr int RPW = BM / 8;                     // routed rows per row group: a group's scales are one dword copy per stage
+    static_assert(RPW <= 32, "a row group's scales fill at most the 32 dwords of its slot");
+    constexpr int kCopies = NCA + 8 + 2;            // vmem operations per copying wavefront and stage
+    // s_waitcnt immediate for vmcnt((NS - 2) kCopies), lgkmcnt(0): vmcnt's low four bits, then its two high bits at 14
+    constexpr int kLater = (NS - 2) * kCopies;
+    constexpr int kWaitNext = 0x0070 | (kLater & 15) | ((kLater >> 4) << 14);
+    constexpr int kSaBytes = kMoeSaBytes;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -212,45 +231,23 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     const int wn = wave & 3, wm = wave >> 2;
     const int half = lane >> 5;
 
-    // workgroup -> (row tile mt, column tile nt).  The grid has max_tiles * NT workgroups (a multiple of
-    // 8), of which ntiles * NT are live; XCD x (= blockIdx % 8) takes the x-th eighth of the live logical
-    // ids in order, so the ~32 workgroups resident on an XCD are neighbours.  Logical order: expert by
-    // expert; inside an expert column tile by column tile, the expert's row tiles innermost: neighbours
-    // share their weight tile (same nt) or their routed rows (same mt), which the XCD's L2 then
-    // fetches once.
-    const int NT = UP ? (p.I >> 7) : (p.H + kMoeBN - 1) / kMoeBN;
-    const int live = p.ntiles[0] * NT, per_xcd = (live + 7) >> 3;
-    const int bid = blockIdx.x;
-    const int logical = (bid & 7) * per_xcd + (bid >> 3);
-    if ((bid >> 3) >= per_xcd || logical >= live) return;   // uniform: before any barrier
-    int nt, mt;
-    {
-        const int mt0 = logical / NT;               // some row tile of the expert whose block holds `logical`
-        const int ee = p.tile_expert[mt0], o0 = p.offsets[ee], o1 = p.offsets[ee + 1];
-        const int first = mt0 - (p.tile_row0[mt0] - o0) / p.bm;       // the expert's first row tile
-        const int cnt = (o1 - o0 + p.bm - 1) / p.bm;                  // and how many it has
-        const int off = logical - first * NT;                         // in [0, cnt * NT)
-        nt = off / cnt;
-        mt = first + (off - nt * cnt);
-    }
-
     const int e = p.tile_expert[mt], row0 = p.tile_row0[mt], rows = p.tile_rows[mt];
     const int KB = UP ? p.H : p.I;                  // bytes (= elements) per row of both operands
     const int nK = KB >> 7;
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
 
     // ---- copies: wavefronts 0-3 (one per SIMD) issue them: per stage instructions c + 4 n of the
-    // routed rows (n < 2 NA) and of the weights (n < 8), and the dword copies of the row scales for
+    // routed rows (n < NCA) and of the weights (n < 8), and the dword copies of the row scales for
     // the row groups c and c + 4.  Wavefronts 4-7 issue no memory traffic in the loop: four issuers
     // measured 5-10 % faster than eight.  (An L2 warm-up by the idle wavefronts, as in the bf16 GEMM,
     // was tried and is harmful here: an XCD's L2 holds 128 KB per CU, less than the LDS stages
     // already in flight, so lines touched early are evicted before the copies ask for them.) ----
     const bool copier = wave < 4;
     const int c4 = wave & 3;
-    unsigned a_off[2 * NA], b_off[8], s_off[2];
+    unsigned a_off[NCA], b_off[8], s_off[2];
     {
 #pragma unroll
-        for (int n = 0; n < 2 * NA; ++n) {
+        for (int n = 0; n < NCA; ++n) {
             const int i = c4 + 4 * n;
             const int r = min(kt_dma_row(i, lane), rows - 1);         // rows past the tile re-read its last row
             const int src = UP ? p.sorted_tok[row0 + r] : row0 + r;
@@ -276,17 +273,19 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
                                   : (const char*)(p.w2 + (size_t)e * (size_t)p.H * (size_t)p.I);
     const char* const s_base = UP ? (const char*)p.xs : (const char*)p.as;
     const unsigned lds_copy_base = lds_base + c4 * 1024;
-    const unsigned sa_base = (unsigned)(size_t)LDS_PTR(float, sa_stage) + c4 * 256;
+    const unsigned sa_base = (unsigned)(size_t)LDS_PTR(float, sa_stage) + c4 * 128;
     auto dma_stage = [&](int U, auto sc) __attribute__((always_inline)) {
         constexpr int s = decltype(sc)::value;
-        static_for<0, 2 * NA>([&](auto n) __attribute__((always_inline)) {
+        static_for<0, NCA>([&](auto n) __attribute__((always_inline)) {
             dma_to_lds_16B<s * kStage + n.value * 4096>(a_base + (size_t)U * 128, a_off[n.value], lds_copy_base);
         });
         static_for<0, 8>([&](auto n) __attribute__((always_inline)) {
             dma_to_lds_16B<s * kStage + kStageA + n.value * 4096>(b_base + (size_t)U * 128, b_off[n.value], lds_copy_base);
         });
-        dma_to_lds_4B<s * kSaBytes>(s_base + (size_t)U * 4, s_off[0], sa_base);
-        dma_to_lds_4B<s * kSaBytes + 1024>(s_base + (size_t)U * 4, s_off[1], sa_base);
+        if (lane < 32) {                            // a slot holds 32 dwords: the upper half of the wavefront stays out
+            dma_to_lds_4B<s * kSaBytes>(s_base + (size_t)U * 4, s_off[0], sa_base);
+            dma_to_lds_4B<s * kSaBytes + 512>(s_base + (size_t)U * 4, s_off[1], sa_base);
+        }
     };
 
     // ---- weight block scales of all stages into LDS (read back as wavefront-uniform broadcasts; a
@@ -306,15 +305,15 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-            a_addr[ks][q] = lds_base + kt_offset((BM / 2) * wm + (lane & 31), 4 * ks + 2 * half + q);
+            a_addr[ks][q] = lds_base + kt_offset(kW0 * wm + (lane & 31), 4 * ks + 2 * half + q);
             b_addr[ks][q] = lds_base + kStageA + kt_offset(64 * wn + (lane & 31), 4 * ks + 2 * half + q);
         }
-    // row scale of routed row m of the tile: copied by wavefront m / RPW as its dword m % RPW
+    // row scale of routed row m of the tile: dword m % RPW of row group m / RPW
     int sa_idx[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        const int m = (BM / 2) * wm + 32 * mb + (lane & 31);
-        sa_idx[mb] = (m / RPW) * 64 + (m % RPW);
+        const int m = min(kW0 * wm + 32 * mb + (lane & 31), BM - 1);     // (a block that does not exist reads a valid slot)
+        sa_idx[mb] = (m / RPW) * 32 + (m % RPW);
     }
     auto frag = [&](unsigned addr0, unsigned addr1, int imm) __attribute__((always_inline)) -> i32x8 {
         const i32x4 lo = *LDS_PTR(i32x4, (size_t)(addr0 + imm));
@@ -336,21 +335,21 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // ---- prologue: two stages in flight ----
+    // ---- prologue: NS - 1 stages in flight ----
     if (copier) {
         dma_stage(0, IntC<0>{});
-        if (1 < nK) dma_stage(1, IntC<1>{});
+        if (NS > 2 && 1 < nK) dma_stage(1, IntC<1>{});
     }
 
     auto step = [&](int U, auto sc) __attribute__((always_inline)) {
         constexpr int s = decltype(sc)::value;
-        // stage U has landed once at most the copies of stage U+1 are outstanding
+        // stage U has landed once at most the copies of the stages issued after it (NS - 2 of them) are outstanding
         if (!copier) __builtin_amdgcn_s_waitcnt(0xC07F);                 // lgkmcnt(0): nothing of its own in flight
-        else if (U + 1 < nK) __builtin_amdgcn_s_waitcnt(kWaitNext);      // vmcnt(kCopies), lgkmcnt(0)
+        else if (NS > 2 && U + 1 < nK) __builtin_amdgcn_s_waitcnt(kWaitNext);   // vmcnt(kCopies), lgkmcnt(0)
         else __builtin_amdgcn_s_waitcnt(0x0070);                         // vmcnt(0), lgkmcnt(0)
         asm volatile("" ::: "memory");
         barrier();                                             // stage U visible; stage U-1's buffer is free
-        if (copier && U + 2 < nK) dma_stage(U + 2, IntC<(s + 2) % kMoeStages>{});
+        if (copier && U + NS - 1 < nK) dma_stage(U + NS - 1, IntC<(s + NS - 1) % NS>{});
         const float sb0 = sb_tab[sb_sel0 * kMoeMaxKB + U], sb1 = sb_tab[sb_sel1 * kMoeMaxKB + U];
         const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
         i32x8 fb[2][2];
@@ -359,6 +358,7 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
             fb[in.value][1] = frag(b_addr[1][0], b_addr[1][1], s * kStage + in.value * 4096);
         });
         static_for<0, MB>([&](auto mb) __attribute__((always_inline)) {
+            if (BM == 160 && mb.value == 2 && wm != 0) return;        // rows 160..191 do not exist
             const float sa = sa_stage[s * (kSaBytes / 4) + sa_idx[mb.value]];
             const i32x8 fa0 = frag(a_addr[0][0], a_addr[0][1], s * kStage + mb.value * 4096);
             const i32x8 fa1 = frag(a_addr[1][0], a_addr[1][1], s * kStage + mb.value * 4096);
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     for (int U = 0;;) {
         step(U, IntC<0>{}); if (++U >= nK) break;
         step(U, IntC<1>{}); if (++U >= nK) break;
-        step(U, IntC<2>{}); if (++U >= nK) break;
+        if constexpr (NS > 2) { step(U, IntC<2>{}); if (++U >= nK) break; }
     }
 
     // result layout of a lane: register r of operand `in`, block mb is weight row 32 in + 8 (r/4) + 4 half + r%4
@@ -398,7 +398,7 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
         }
         __builtin_amdgcn_s_waitcnt(0xC07F);
         barrier();                                             // every wavefront is done with the stage buffers
-        float* const ex = (float*)smem;                        // [wm][mb][wn][32]
+        const LdsFloat ex = (LdsFloat)smem;                        // [wm][mb][wn][32]
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
             if (half == 0) ex[((wm * MB + mb) * 4 + wn) * 32 + (lane & 31)] = amax[mb];
@@ -411,7 +411,7 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
             for (int w = 0; w < 4; ++w) am = fmaxf(am, ex[((wm * MB + mb) * 4 + w) * 32 + (lane & 31)]);
             const float scale = quant_scale(am);
             const float inv = 1.0f / scale;
-            const int m = (BM / 2) * wm + 32 * mb + (lane & 31);
+            const int m = kW0 * wm + 32 * mb + (lane & 31);
             if (m < rows) {
                 uint8_t* const dst = p.aq + (size_t)(row0 + m) * p.I + nt * 128 + 32 * wn + 4 * half;
 #pragma unroll
@@ -423,7 +423,7 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     } else {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const int m = (BM / 2) * wm + 32 * mb + (lane & 31);
+            const int m = kW0 * wm + 32 * mb + (lane & 31);
             if (m < rows) {
 #pragma unroll
                 for (int in = 0; in < 2; ++in)
@@ -438,6 +438,43 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
             }
         }
     }
+}
+
+// Kernel: maps the workgroup to its (row tile, column tile) and runs the tile code that fits the tile's rows.
+template <bool UP>
+__global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
+    __shared__ __attribute__((aligned(16))) char smem[kMoeLdsBytes];
+    __shared__ __attribute__((aligned(16))) float sa_stage[3 * kMoeSaBytes / 4];
+    static_assert(kMoeLdsBytes + 3 * kMoeSaBytes + 2 * kMoeMaxKB * 4 <= 160 * 1024, "LDS budget");
+    __shared__ float sb_tab[2 * kMoeMaxKB];          // weight block scale of the tile's two 128-row blocks and every stage
+
+    // workgroup -> (row tile mt, column tile nt).  The grid has max_tiles * NT workgroups (a multiple of
+    // 8), of which ntiles * NT are live; XCD x (= blockIdx % 8) takes the x-th eighth of the live logical
+    // ids in order, so the ~32 workgroups resident on an XCD are neighbours.  Logical order: expert by
+    // expert; inside an expert column tile by column tile, the expert's row tiles innermost: neighbours
+    // share their weight tile (same nt) or their routed rows (same mt), which the XCD's L2 then
+    // fetches once.
+    const int NT = UP ? (p.I >> 7) : (p.H + kMoeBN - 1) / kMoeBN;
+    const int live = p.ntiles[0] * NT, per_xcd = (live + 7) >> 3;
+    const int bid = blockIdx.x;
+    const int logical = (bid & 7) * per_xcd + (bid >> 3);
+    if ((bid >> 3) >= per_xcd || logical >= live) return;   // uniform: before any barrier
+    int nt, mt;
+    {
+        const int mt0 = logical / NT;               // some row tile of the expert whose block holds `logical`
+        const int ee = p.tile_expert[mt0], o0 = p.offsets[ee], o1 = p.offsets[ee + 1];
+        const int first = mt0 - (p.tile_row0[mt0] - o0) / p.bm;       // the expert's first row tile
+        const int cnt = moe_row_tiles(o1 - o0, p.bm);                 // and how many it has
+        const int off = logical - first * NT;                         // in [0, cnt * NT)
+        nt = off / cnt;
+        mt = first + (off - nt * cnt);
+    }
+    const int rows = p.tile_rows[mt];                // uniform
+    const LdsChar tiles = LDS_PTR(char, smem);
+    const LdsFloat sa = LDS_PTR(float, sa_stage), sb = LDS_PTR(float, sb_tab);
+    if (rows > 128) moe_gemm_tile<UP, 160>(p, mt, nt, tiles, sa, sb);
+    else if (rows > 64) moe_gemm_tile<UP, 128>(p, mt, nt, tiles, sa, sb);
+    else moe_gemm_tile<UP, 64>(p, mt, nt, tiles, sa, sb);
 }
 
 // ------------------------------------------------------------------------------------
@@ -474,13 +511,8 @@ int moe_launch(const MoeParams& p, int first, int last, hipStream_t stream) {
                            (on(0) ? 1 : 0) | (on(1) ? 2 : 0));
     auto grid8 = [](long long n) { return dim3((unsigned)((n + 7) / 8 * 8)); };   // the tile order wants a multiple of 8
     const dim3 g_up = grid8((long long)p.max_tiles * (p.I / 128)), g_dn = grid8((long long)p.max_tiles * ((p.H + kMoeBN - 1) / kMoeBN));
-    if (p.bm == 128) {
-        if (on(2)) hipLaunchKernelGGL((moe_gemm<true, 128>), g_up, dim3(512), 0, stream, p);
-        if (on(3)) hipLaunchKernelGGL((moe_gemm<false, 128>), g_dn, dim3(512), 0, stream, p);
-    } else {
-        if (on(2)) hipLaunchKernelGGL((moe_gemm<true, 64>), g_up, dim3(512), 0, stream, p);
-        if (on(3)) hipLaunchKernelGGL((moe_gemm<false, 64>), g_dn, dim3(512), 0, stream, p);
-    }
+    if (on(2)) hipLaunchKernelGGL((moe_gemm<true>), g_up, dim3(512), 0, stream, p);
+    if (on(3)) hipLaunchKernelGGL((moe_gemm<false>), g_dn, dim3(512), 0, stream, p);
     if (on(4)) hipLaunchKernelGGL(moe_combine, dim3((unsigned)(((p.H / 8 + 255) / 256) * p.T)), dim3(256), 0, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }

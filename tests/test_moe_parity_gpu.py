@@ -194,14 +194,18 @@ def test_small_configurations(cfg, row_tile):
     sanity_net(g["y"], oracle.moe_ref(**d), str(w))
 
 
+# every token goes to both experts, so an expert has T rows.  With 128-row tiles: 700 = 5 x 128 + 60 (a 64-row tail),
+# 300 = 128 + 128 + 44, 280 = 128 + 128 + 24, 150 and 160 (one tile on the 160-row code, 160 being its limit),
+# 161 = 128 + 33 (one row too many for a single tile).  With 64-row tiles the same sizes give up to 11 tiles.
 @pytest.mark.parametrize("row_tile", [64, 128])
-def test_many_rows_per_expert_span_several_row_tiles(row_tile):
-    w = I.MoeWorkload("t", 700, 77, H=256, I=256, E=2, KTOP=2, EP=1)      # 700 rows per expert: 11 tiles of 64 / 6 of 128, ragged last
+@pytest.mark.parametrize("T", [700, 300, 280, 150, 160, 161, 90, 96, 97])
+def test_many_rows_per_expert_span_several_row_tiles(T, row_tile):
+    w = I.MoeWorkload("t", T, 77 + T, H=256, I=256, E=2, KTOP=2, EP=1)
     d = I.make_moe(w)
     print("moe case", w, "row tile", row_tile, flush=True)
     g = run(d, row_tile)
     check_routing(w, d, g)
-    tokens = [0, 1, 63, 64, 65, 350, 639, 640, 698, 699]
+    tokens = sorted({t for t in (0, 1, 63, 64, 65, 127, 128, 129, 149, 255, 256, 257, T - 45, T - 2, T - 1) if 0 <= t < T})
     check_stage1(w, d, g, tokens)
     check_y(w, d, g, tokens)
     sanity_net(g["y"], oracle.moe_ref(**d), str(w))
@@ -215,7 +219,7 @@ def test_no_local_expert_at_all():
     assert not g["y"].any() and int(g["offsets"][w.E]) == 0 and np.all(g["pos"] == -1)
 
 
-@pytest.mark.parametrize("row_tile", [0, 128])
+@pytest.mark.parametrize("row_tile", [0, 128, 64])
 def test_paper_shape_on_sampled_tokens(row_tile):
     w = I.MOE_WORKLOADS["M1024"]
     d = I.make_moe(w)

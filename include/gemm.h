@@ -55,6 +55,10 @@ int gemm_bf16(const void *a, const void *b, void *c, int M, int N, int K,
 int gemm_bf16_tile(const void *a, const void *b, void *c, int M, int N, int K,
                    long long lda, long long ldb, long long ldc, int b_is_nk, int tile, void *stream);
 
+/* The tile gemm_bf16 takes for an M x N result when its operands qualify for the matrix-core kernel: 64, 128,
+ * 1284 or 256 as described above (0 for invalid sizes).  Host-only helper, for tuning and for tests. */
+int gemm_bf16_auto_tile(int M, int N);
+
 /* Algorithmic FLOPs of one gemm_bf16 call: 2*M*N*K (0 for invalid sizes).  Host-only helper. */
 double gemm_bf16_flops(int M, int N, int K);
 

@@ -40,6 +40,8 @@ def load_library(build_if_missing: bool = True):
         lib.gemm_bf16.argtypes = [p, p, p, i, i, i, ll, ll, ll, i, p]
         lib.gemm_bf16_tile.restype = i
         lib.gemm_bf16_tile.argtypes = [p, p, p, i, i, i, ll, ll, ll, i, i, p]
+        lib.gemm_bf16_auto_tile.restype = i
+        lib.gemm_bf16_auto_tile.argtypes = [i, i]
         lib.gemm_bf16_flops.restype = ctypes.c_double
         lib.gemm_bf16_flops.argtypes = [i, i, i]
         lib.moe_ffn_fp8_workspace_bytes.restype = ctypes.c_size_t

@@ -37,6 +37,11 @@ extern "C" int gemm_bf16(const void* a, const void* b, void* c, int M, int N, in
     return gemm_bf16_tile(a, b, c, M, N, K, lda, ldb, ldc, b_is_nk, 0, stream);
 }
 
+extern "C" int gemm_bf16_auto_tile(int M, int N) {
+    if (M <= 0 || N <= 0) return 0;
+    return gemm_auto_tile(M, N);
+}
+
 extern "C" double gemm_bf16_flops(int M, int N, int K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0.0;
     return 2.0 * (double)M * (double)N * (double)K;

@@ -441,11 +441,15 @@ static void launch_tiled(GemmParams p, int b_is_nk, hipStream_t stream) {
 //                                                      depth of the copy pipeline has to come from one workgroup;
 //   else                                            -> 64 x 64 tiles: the time is the L2 -> LDS traffic of the
 //                                                      busiest CU, and four times the tiles spread it out.
+int gemm_auto_tile(int M, int N) {
+    const long long large_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+    const long long small_tiles = (long long)((M + 127) / 128) * ((N + 127) / 128);
+    return large_tiles >= 128 ? 256 : small_tiles > 256 ? 128 : small_tiles > 112 ? 1284 : 64;
+}
+
 int gemm_launch(GemmParams p, int b_is_nk, bool tiled, int tile, hipStream_t stream) {
     if (tiled) {
-        const long long large_tiles = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256);
-        const long long small_tiles = (long long)((p.M + 127) / 128) * ((p.N + 127) / 128);
-        if (tile == 0) tile = large_tiles >= 128 ? 256 : small_tiles > 256 ? 128 : small_tiles > 112 ? 1284 : 64;
+        if (tile == 0) tile = gemm_auto_tile(p.M, p.N);
         if (tile == 2564) launch_tiled<TileLarge4>(p, b_is_nk, stream);
         else if (tile == 256) launch_tiled<TileLarge>(p, b_is_nk, stream);
         else if (tile == 64) launch_tiled<TileTiny>(p, b_is_nk, stream);

@@ -115,11 +115,17 @@ GEMM_HEADER = os.path.join(ROOT, "include", "gemm.h")
 def test_gemm_header_symbols_are_exported(lib):
     src = re.sub(r"/\*.*?\*/", "", open(GEMM_HEADER).read(), flags=re.S)
     names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", src)
-    assert set(names) == {"gemm_bf16", "gemm_bf16_tile", "gemm_bf16_flops"}
+    assert set(names) == {"gemm_bf16", "gemm_bf16_tile", "gemm_bf16_auto_tile", "gemm_bf16_flops"}
     for name in names:
         assert hasattr(lib, name), name
     assert lib.gemm_bf16_flops(1024, 512, 256) == 2.0 * 1024 * 512 * 256
     assert lib.gemm_bf16_flops(0, 5, 5) == 0.0
+    # the tile rule at the paper's square sizes and at the cross-overs it was measured on
+    lib.gemm_bf16_auto_tile.restype = ctypes.c_int
+    lib.gemm_bf16_auto_tile.argtypes = [ctypes.c_int, ctypes.c_int]
+    want = {1024: 64, 1280: 64, 1536: 1284, 2048: 1284, 2304: 128, 2560: 128, 3072: 256, 4096: 256, 8192: 256, 16384: 256}
+    assert {s: lib.gemm_bf16_auto_tile(s, s) for s in want} == want
+    assert lib.gemm_bf16_auto_tile(0, 8) == 0 and lib.gemm_bf16_auto_tile(64, 1 << 20) == 256
 
 
 def test_gemm_argument_errors_are_reported_without_a_gpu(lib):

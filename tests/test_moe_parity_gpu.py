@@ -219,9 +219,11 @@ def test_no_local_expert_at_all():
     assert not g["y"].any() and int(g["offsets"][w.E]) == 0 and np.all(g["pos"] == -1)
 
 
-@pytest.mark.parametrize("row_tile", [0, 128, 64])
-def test_paper_shape_on_sampled_tokens(row_tile):
-    w = I.MOE_WORKLOADS["M1024"]
+# M1024: about 16 rows per expert (the 64-row code); M8192: 128 +- 11 rows per expert, so that the 64-, 128- and
+# 160-row codes all run at the paper's H and I in one call
+@pytest.mark.parametrize("name,row_tile", [("M1024", 0), ("M1024", 64), ("M8192", 0)])
+def test_paper_shape_on_sampled_tokens(name, row_tile):
+    w = I.MOE_WORKLOADS[name]
     d = I.make_moe(w)
     print("moe workload", w, "local slots", w.local_slots(d["ids"]), "row tile", row_tile, flush=True)
     g = run(d, row_tile)

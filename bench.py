@@ -265,7 +265,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--workload", default="C3",
+                    help="attention: C1..C5 (C3 = the headline config), N8K, P1024..P16384 (the paper's shape); "
+                         "bf16 GEMM: G1024..G16384, with a trailing T for B stored [N,K]; fused MoE FP8: M1024..M16384")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU reference leg (profiling runs)")
     ap.add_argument("--vendor-context", action="store_true",
                     help="also time the library PyTorch ships for the same operation on the same inputs (torch.matmul / "

@@ -81,7 +81,8 @@ int moe_ffn_fp8_ex(const void *x, const int *ids, const float *wts,
  *   8 xq         e4m3  [T, H]     quantized activations        9 xs   fp32 [T, H/128] their scales
  *                (both only for tokens that have a local slot)
  *  10 aq         e4m3  [rows, I]  quantized intermediate      11 as   fp32 [rows, I/128]
- *  12 o          fp32  [rows, H]  down-projection rows
+ *  12 o          fp32  [rows, H]  down-projection rows of tokens with two or more local slots (the row of a token
+ *                with a single local slot goes straight to y as wts * row, which is all its sum has; its o is not written)
  * (1-5 are internal scheduling tables.)  Host only.
  */
 long long moe_ffn_fp8_workspace_offset(int T, int H, int I, int E, int KTOP, int part);

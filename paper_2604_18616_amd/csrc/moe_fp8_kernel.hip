@@ -11,8 +11,10 @@
 //   moe_gemm<UP>  per (row tile, 128 intermediate columns): gate and up products on
 //                 v_mfma_scale_f32_32x32x64_f8f6f4, block scales applied per 128-deep stage,
 //                 SiLU gate, requantization of the 128-column group, FP8 store;
-//   moe_gemm<DN>  per (row tile, 256 output columns): down product, fp32 rows to the workspace;
-//   moe_combine   y[t] = sum over local slots of weight * row, rounded once to bf16.
+//   moe_gemm<DN>  per (row tile, 256 output columns): down product; the row of a token with a single local slot
+//                 goes straight to y (weight * row, rounded once), the others as fp32 rows to the workspace;
+//   moe_combine   y[t] = sum over local slots of weight * row, rounded once to bf16, for the tokens with
+//                 two or more local slots; zeros for those with none.
 // With 16 to 256 rows per expert the products are bound by streaming the expert weights from
 // HBM (each byte is used for 2 x rows FLOPs), so the grouped product keeps three 40-48 KB stages
 // of direct-to-LDS copies in flight per workgroup and does nothing clever with the MFMAs.
@@ -335,6 +337,27 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int mt, int nt
         __builtin_amdgcn_sched_barrier(0);
     };
 
+    // ---- down product: where each row goes.  A row that is the only local slot of its token is that token's
+    // whole sum and is written to y directly.  The lookup (row -> token -> its slots -> weight: three dependent
+    // loads) is done here, before the loop, by the wavefronts that do not copy (a copying wavefront would have
+    // to wait for it before it may issue its first copies): thread 256 + m takes row m and hands token and
+    // weight over through LDS once the stage buffers are free, after the loop ----
+    int look_tok = -1;
+    float look_w = 0.0f;
+    if constexpr (!UP) {
+        const int m = tid - 256;
+        if (m >= 0 && m < rows) {
+            const int t = p.sorted_tok[row0 + m];
+            int nlocal = 0, slot = 0;
+            for (int k = 0; k < p.KTOP; ++k) {
+                const int rk = p.pos[t * p.KTOP + k];
+                nlocal += rk >= 0 ? 1 : 0;
+                if (rk == row0 + m) slot = k;
+            }
+            if (nlocal == 1) { look_tok = t; look_w = p.wts[t * p.KTOP + slot]; }
+        }
+    }
+
     // ---- prologue: NS - 1 stages in flight ----
     if (copier) {
         dma_stage(0, IntC<0>{});
@@ -421,10 +444,22 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int mt, int nt
             }
         }
     } else {
+        // A row that is the only local slot of its token is that token's whole sum: weight * row, rounded once
+        // to bf16, goes to y directly (bit for bit what the combine step computes from the fp32 row) and the
+        // fp32 row is neither written nor read again.  Other rows go to the workspace for moe_combine.
+        static_assert(BM <= 256, "one lookup thread per row");
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        barrier();                                             // every wavefront is done with the stage buffers
+        const LdsFloat hand = (LdsFloat)smem;                  // [row][token bits, weight]
+        if (tid >= 256 && tid - 256 < BM) { hand[2 * (tid - 256)] = __int_as_float(look_tok); hand[2 * (tid - 256) + 1] = look_w; }
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        barrier();
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const int m = kW0 * wm + 32 * mb + (lane & 31);
             if (m < rows) {
+                const int dst = __float_as_int(hand[2 * m]);
+                const float w = hand[2 * m + 1];
 #pragma unroll
                 for (int in = 0; in < 2; ++in)
 #pragma unroll
@@ -432,7 +467,13 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int mt, int nt
                         const int c = nt * kMoeBN + 64 * wn + 32 * in + 8 * g4 + 4 * half;
                         if (c < p.H) {
                             const f32x4 v = {acc[in][mb][4 * g4], acc[in][mb][4 * g4 + 1], acc[in][mb][4 * g4 + 2], acc[in][mb][4 * g4 + 3]};
-                            *(f32x4*)(p.o + (size_t)(row0 + m) * p.H + c) = v;
+                            if (dst >= 0) {
+                                typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+                                const bf16x4 out = {(__bf16)fmaf(w, v[0], 0.0f), (__bf16)fmaf(w, v[1], 0.0f), (__bf16)fmaf(w, v[2], 0.0f), (__bf16)fmaf(w, v[3], 0.0f)};   // as moe_combine: 0 + w * v
+                                *(bf16x4*)(p.y + (size_t)dst * p.H + c) = out;
+                            } else {
+                                *(f32x4*)(p.o + (size_t)(row0 + m) * p.H + c) = v;
+                            }
                         }
                     }
             }
@@ -478,13 +519,17 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
 }
 
 // ------------------------------------------------------------------------------------
-// Combine: y[t][c] = sum over local slots k (ascending) of wts[t][k] * o[pos[t][k]][c], bf16.
+// Combine: y[t][c] = sum over local slots k (ascending) of wts[t][k] * o[pos[t][k]][c], bf16.  Tokens with exactly
+// one local slot were written by the down product.
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void moe_combine(MoeParams p) {
     const int cblocks = (p.H / 8 + 255) / 256;
     const int t = blockIdx.x / cblocks;
     const int c = ((blockIdx.x - t * cblocks) * 256 + threadIdx.x) * 8;
     if (c >= p.H) return;
+    int nlocal = 0;
+    for (int k = 0; k < p.KTOP; ++k) nlocal += p.pos[t * p.KTOP + k] >= 0 ? 1 : 0;
+    if (nlocal == 1) return;
     float acc[8] = {};
     for (int k = 0; k < p.KTOP; ++k) {
         const int r = p.pos[t * p.KTOP + k];

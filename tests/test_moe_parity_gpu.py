@@ -143,7 +143,8 @@ def check_slots(w, d, g, slots):
         o_ref = oracle.moe_down(g["aq"][r], g["as_"][r], d["w2"], d["s2"], e)
         deq = VALS[g["aq"][r]] * np.repeat(g["as_"][r].astype(np.float64), 128)
         do = mfma_uncertainty(deq, dequant_weights(d["w2"][e], d["s2"][e]))
-        assert np.all(np.abs(g["o"][r] - o_ref) <= do + 1e-30), ("down row", t, k, float((np.abs(g["o"][r] - o_ref) / do).max()))
+        if ((d["ids"][t] >= 0) & (d["ids"][t] < w.E)).sum() > 1:   # the fp32 row exists only for tokens with several local slots: a single one goes straight to y (check_y)
+            assert np.all(np.abs(g["o"][r] - o_ref) <= do + 1e-30), ("down row", t, k, float((np.abs(g["o"][r] - o_ref) / do).max()))
         rows[(t, k)] = (o_ref, do)
     return rows
 

@@ -98,9 +98,15 @@ __device__ __forceinline__ void route_block(const MoeParams& p) {
     const int tid = threadIdx.x, wave = tid >> 6, E = p.E, n = p.T * p.KTOP;
     for (int i = tid; i < 16 * 256; i += 1024) wcnt[i] = 0;
     __syncthreads();
-    for (int i = tid; i < n; i += 1024) {
-        const int e = p.ids[i];
-        if (e >= 0 && e < E) atomicAdd(&wcnt[wave * 256 + e], 1);
+    // (both passes take kRU slots per thread and iteration with the loads issued together: this workgroup is
+    // alone with the latency of its loads, and under the quantization blocks' traffic that latency is long)
+    constexpr int kRU = 4;
+    for (int i0 = tid; i0 < n; i0 += 1024 * kRU) {
+        int e[kRU];
+#pragma unroll
+        for (int j = 0; j < kRU; ++j) { const int i = i0 + 1024 * j; e[j] = i < n ? p.ids[i] : -1; }
+#pragma unroll
+        for (int j = 0; j < kRU; ++j) if (e[j] >= 0 && e[j] < E) atomicAdd(&wcnt[wave * 256 + e[j]], 1);
     }
     __syncthreads();
     if (tid < 256) {                         // expert tid: total, and each wavefront's offset inside the expert
@@ -132,23 +138,31 @@ __device__ __forceinline__ void route_block(const MoeParams& p) {
         if (tid == E - 1) { p.offsets[E] = rows_scan[tid]; p.ntiles[0] = tiles_scan[tid]; }
     }
     __syncthreads();
-    for (int i = tid; i < n; i += 1024) {
-        const int e = p.ids[i];
-        int r = -1;
-        if (e >= 0 && e < E) {
-            r = atomicAdd(&wcnt[wave * 256 + e], 1);
-            p.sorted_tok[r] = i / p.KTOP;
+    for (int i0 = tid; i0 < n; i0 += 1024 * kRU) {
+        int e[kRU];
+#pragma unroll
+        for (int j = 0; j < kRU; ++j) { const int i = i0 + 1024 * j; e[j] = i < n ? p.ids[i] : -1; }
+#pragma unroll
+        for (int j = 0; j < kRU; ++j) {
+            const int i = i0 + 1024 * j;
+            if (i >= n) break;
+            int r = -1;
+            if (e[j] >= 0 && e[j] < E) {
+                r = atomicAdd(&wcnt[wave * 256 + e[j]], 1);
+                p.sorted_tok[r] = i / p.KTOP;
+            }
+            p.pos[i] = r;
         }
-        p.pos[i] = r;
     }
 }
 
 // ------------------------------------------------------------------------------------
 // Activation quantization: 32 lanes per group of 128 features, 4 features per lane.
 // ------------------------------------------------------------------------------------
+constexpr int kMoeQuantGroups = 8;           // groups of 128 features one 32-lane unit quantizes, all loaded up front (4: 15 % slower)
 __device__ __forceinline__ void quant_x_block(const MoeParams& p, unsigned block) {
     // 32 lanes take kQG consecutive groups of one token (all loads issued before the first use)
-    constexpr int kQG = 4;
+    constexpr int kQG = kMoeQuantGroups;
     const int gpt = p.H / 128;                                    // groups per token
     const int cpt = (gpt + kQG - 1) / kQG;                        // 32-lane work items per token
     const long long item = (long long)block * 32 + (threadIdx.x >> 5);
@@ -550,7 +564,7 @@ __global__ __launch_bounds__(256) void moe_combine(MoeParams p) {
 
 int moe_launch(const MoeParams& p, int first, int last, hipStream_t stream) {
     auto on = [&](int stage) { return first <= stage && stage <= last; };
-    const long long items = (long long)p.T * ((p.H / 128 + 3) / 4);   // quantization: 4 groups of a token per 32 lanes
+    const long long items = (long long)p.T * ((p.H / 128 + kMoeQuantGroups - 1) / kMoeQuantGroups);   // quantization: kMoeQuantGroups groups of a token per 32 lanes
     if (on(0) || on(1))
         hipLaunchKernelGGL(moe_prepare, dim3(1 + (on(1) ? (unsigned)((items + 31) / 32) : 0u)), dim3(1024), 0, stream, p,
                            (on(0) ? 1 : 0) | (on(1) ? 2 : 0));

@@ -25,9 +25,9 @@ size_t moe_workspace_layout(int T, int H, int I, int E, int KTOP, size_t off[13]
     take(0, sizeof(int) * (E + 1));          // offsets
     take(1, sizeof(int) * E);                // cursor
     take(2, sizeof(int));                    // ntiles
-    take(3, sizeof(int) * max_tiles);        // tile_expert
-    take(4, sizeof(int) * max_tiles);        // tile_row0
-    take(5, sizeof(int) * max_tiles);        // tile_rows
+    take(3, 4 * sizeof(int) * max_tiles);    // tile_rec
+    take(4, sizeof(int));                    // (not in use)
+    take(5, sizeof(int));                    // (not in use)
     take(6, sizeof(int) * slots);            // sorted_tok
     take(7, sizeof(int) * slots);            // pos
     take(8, (size_t)T * H);                  // xq
@@ -79,7 +79,7 @@ extern "C" int moe_ffn_fp8_ex(const void* x, const int* ids, const float* wts,
     p.bm = bm_override ? bm_override : 128;
     p.max_tiles = (int)(((size_t)T * KTOP + p.bm - 1) / p.bm + E);
     p.offsets = (int*)(ws + off[0]); p.cursor = (int*)(ws + off[1]); p.ntiles = (int*)(ws + off[2]);
-    p.tile_expert = (int*)(ws + off[3]); p.tile_row0 = (int*)(ws + off[4]); p.tile_rows = (int*)(ws + off[5]);
+    p.tile_rec = (MoeTileRec*)(ws + off[3]);
     p.sorted_tok = (int*)(ws + off[6]); p.pos = (int*)(ws + off[7]);
     p.xq = (uint8_t*)(ws + off[8]); p.xs = (float*)(ws + off[9]);
     p.aq = (uint8_t*)(ws + off[10]); p.as = (float*)(ws + off[11]);

@@ -131,9 +131,7 @@ __device__ __forceinline__ void route_block(const MoeParams& p) {
         p.offsets[tid] = start;
         for (int w = 0; w < 16; ++w) wcnt[w * 256 + tid] += start;
         for (int m = 0; m < nt; ++m) {
-            p.tile_expert[tstart + m] = tid;
-            p.tile_row0[tstart + m] = start + m * p.bm;
-            p.tile_rows[tstart + m] = m == nt - 1 ? cnt[tid] - m * p.bm : p.bm;   // the last tile takes what is left: up to bm + 32 rows
+            p.tile_rec[tstart + m] = MoeTileRec{tid, start, cnt[tid], tstart};
         }
         if (tid == E - 1) { p.offsets[E] = rows_scan[tid]; p.ntiles[0] = tiles_scan[tid]; }
     }
@@ -226,7 +224,7 @@ constexpr int kMoeMaxKB = 64;                       // 128-blocks along k: H, I 
 typedef __attribute__((address_space(3))) char* LdsChar;      // LDS pointers stay typed as such: a generic pointer would
 typedef __attribute__((address_space(3))) float* LdsFloat;    // turn the scale reads into flat loads, which count as vector memory
 template <bool UP, int BM>
-__device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int mt, int nt, LdsChar smem, LdsFloat sa_stage, LdsFloat sb_tab) {
+__device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row0, int rows, int nt, LdsChar smem, LdsFloat sa_stage, LdsFloat sb_tab) {
     constexpr int NS = 3;                           // LDS stages
     constexpr int kStageA = BM * 128, kStageB = kMoeBN * 128, kStage = kStageA + kStageB;
     static_assert(NS * kStage <= kMoeLdsBytes, "stages exceed the workgroup's LDS");
@@ -247,7 +245,6 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int mt, int nt
     const int wn = wave & 3, wm = wave >> 2;
     const int half = lane >> 5;
 
-    const int e = p.tile_expert[mt], row0 = p.tile_row0[mt], rows = p.tile_rows[mt];
     const int KB = UP ? p.H : p.I;                  // bytes (= elements) per row of both operands
     const int nK = KB >> 7;
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
@@ -514,22 +511,17 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     const int bid = blockIdx.x;
     const int logical = (bid & 7) * per_xcd + (bid >> 3);
     if ((bid >> 3) >= per_xcd || logical >= live) return;   // uniform: before any barrier
-    int nt, mt;
-    {
-        const int mt0 = logical / NT;               // some row tile of the expert whose block holds `logical`
-        const int ee = p.tile_expert[mt0], o0 = p.offsets[ee], o1 = p.offsets[ee + 1];
-        const int first = mt0 - (p.tile_row0[mt0] - o0) / p.bm;       // the expert's first row tile
-        const int cnt = moe_row_tiles(o1 - o0, p.bm);                 // and how many it has
-        const int off = logical - first * NT;                         // in [0, cnt * NT)
-        nt = off / cnt;
-        mt = first + (off - nt * cnt);
-    }
-    const int rows = p.tile_rows[mt];                // uniform
+    const MoeTileRec rec = p.tile_rec[logical / NT];             // the expert whose block of ids holds `logical`
+    const int cnt = moe_row_tiles(rec.rows, p.bm);                // its row tiles; the last takes what is left: up to bm + 32 rows
+    const int off = logical - rec.first * NT;                     // in [0, cnt * NT)
+    const int nt = off / cnt, j = off - nt * cnt;                 // column tile, row tile within the expert
+    const int e = rec.expert, row0 = rec.row0 + j * p.bm;
+    const int rows = j == cnt - 1 ? rec.rows - j * p.bm : p.bm;   // uniform
     const LdsChar tiles = LDS_PTR(char, smem);
     const LdsFloat sa = LDS_PTR(float, sa_stage), sb = LDS_PTR(float, sb_tab);
-    if (rows > 128) moe_gemm_tile<UP, 160>(p, mt, nt, tiles, sa, sb);
-    else if (rows > 64) moe_gemm_tile<UP, 128>(p, mt, nt, tiles, sa, sb);
-    else moe_gemm_tile<UP, 64>(p, mt, nt, tiles, sa, sb);
+    if (rows > 128) moe_gemm_tile<UP, 160>(p, e, row0, rows, nt, tiles, sa, sb);
+    else if (rows > 64) moe_gemm_tile<UP, 128>(p, e, row0, rows, nt, tiles, sa, sb);
+    else moe_gemm_tile<UP, 64>(p, e, row0, rows, nt, tiles, sa, sb);
 }
 
 // ------------------------------------------------------------------------------------

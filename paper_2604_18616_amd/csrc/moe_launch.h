@@ -7,6 +7,17 @@
 
 constexpr int kMoeBM = 64;   // smallest row tile (routed token slots of one expert) of the grouped products: sizes the tile tables
 
+// What a workgroup of the grouped products needs to know about the expert its row tile belongs to, in one
+// 16-byte load: the tile's own first row and row count follow from these by arithmetic (moe_row_tiles), so the
+// chain of dependent loads in front of a workgroup's first copy is: number of tiles -> this record -> (gate/up
+// only) the tokens of its rows.
+struct MoeTileRec {
+    int expert;               // the expert
+    int row0;                 // its first sorted row
+    int rows;                 // its number of rows
+    int first;                // index of its first row tile
+};
+
 struct MoeParams {
     const __bf16* x; const int* ids; const float* wts;
     const uint8_t* w13; const float* s13; const uint8_t* w2; const float* s2;
@@ -18,9 +29,7 @@ struct MoeParams {
     int* offsets;             // [E + 1] first sorted row of each expert
     int* cursor;              // [E]     scatter cursors
     int* ntiles;              // [1]     row tiles in use
-    int* tile_expert;         // [max_tiles]
-    int* tile_row0;           // [max_tiles] first sorted row of the tile
-    int* tile_rows;           // [max_tiles] rows in the tile (1..bm)
+    MoeTileRec* tile_rec;     // [max_tiles] one record per row tile
     int* sorted_tok;          // [T*KTOP] token of each sorted row
     int* pos;                 // [T*KTOP] sorted row of slot (t, k), or -1 if the slot is not local
     uint8_t* xq; float* xs;   // [T, H] codes, [T, H/128] scales

@@ -323,10 +323,11 @@ constexpr float kBig = 18446744073709551616.0f;   // 2^64: bound on a partial ro
 #define ATTN_PF 3
 #endif
 #ifndef ATTN_SM_PRIO
-#define ATTN_SM_PRIO 2
+#define ATTN_SM_PRIO 0
 #endif
 constexpr int kPF = ATTN_PF;           // MFMA operands kept in flight from LDS (ring of 4-register fragments)
-constexpr int kSmPrio = ATTN_SM_PRIO;  // wave priority while in the softmax (0 elsewhere)
+constexpr int kSmPrio = ATTN_SM_PRIO;  // wave priority while in the softmax (0 elsewhere).  Measured 0..3: with the max-free
+                                       // softmax 0 is 1.2-1.5 % faster than 1-3 at D = 128 (a raised priority helped the older, longer softmax)
 
 template <int V> struct IntC { static constexpr int value = V; };
 // compile-time loop: f(IntC<I>{}) for I = BEGIN .. END-1, everything inlined

@@ -87,6 +87,11 @@ int moe_ffn_fp8_ex(const void *x, const int *ids, const float *wts,
  */
 long long moe_ffn_fp8_workspace_offset(int T, int H, int I, int E, int KTOP, int part);
 
+/* Row tiles (workgroups per column tile) an expert with `rows` routed rows is cut into for row_tile = 0, 64 or
+ * 128 as in moe_ffn_fp8_ex: tiles of row_tile rows and a remainder, except that an expert with row_tile + 1 ..
+ * row_tile + 32 rows gets a single tile.  -1 for a negative count or another row_tile.  Host-only helper. */
+int moe_ffn_fp8_row_tiles(int rows, int row_tile);
+
 /* Algorithmic FLOPs per routed (token, local expert) pair: 2 * (2I*H + H*I).  Host-only helper. */
 double moe_ffn_fp8_flops_per_pair(int H, int I);
 

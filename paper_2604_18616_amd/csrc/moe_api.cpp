@@ -94,6 +94,11 @@ extern "C" int moe_ffn_fp8(const void* x, const int* ids, const float* wts,
     return moe_ffn_fp8_ex(x, ids, wts, w13, s13, w2, s2, y, T, H, I, E, KTOP, workspace, workspace_bytes, 0, 4, 0, stream);
 }
 
+extern "C" int moe_ffn_fp8_row_tiles(int rows, int row_tile) {
+    if (rows < 0 || (row_tile != 0 && row_tile != 64 && row_tile != 128)) return -1;
+    return moe_row_tiles(rows, row_tile ? row_tile : 128);
+}
+
 extern "C" double moe_ffn_fp8_flops_per_pair(int H, int I) {
     if (H <= 0 || I <= 0) return 0.0;
     return 6.0 * (double)H * (double)I;

@@ -74,16 +74,6 @@ __device__ __forceinline__ unsigned quant_pack4(float v0, float v1, float v2, fl
     return (unsigned)p;
 }
 
-// Row tiles of an expert with cnt rows: tiles of bm rows and a remainder.  An expert with one full tile and
-// at most 32 rows more gets a single tile of up to bm + 32 rows (one more 32-row MFMA block instead of a
-// second copy of every weight tile: 13 % on the whole call where experts have about bm rows).  With two or
-// more full tiles the remainder stays a tile of its own: measured, the short tiles then cost little (their
-// weights are L2 hits) and fill the last round of workgroups, which equal long tiles leave mostly idle.
-__device__ __forceinline__ int moe_row_tiles(int cnt, int bm) {
-    const int n = cnt / bm, r = cnt - n * bm;
-    return (n == 1 && r <= 32) ? 1 : n + (r > 0 ? 1 : 0);
-}
-
 // ------------------------------------------------------------------------------------
 // Routing: one workgroup of 16 wavefronts.  Thousands of slots land on a few dozen counters, so each
 // wavefront counts into a histogram of its own (LDS atomics without a return value); the per-expert

@@ -154,10 +154,23 @@ def test_moe_header_symbols_are_exported(lib):
     src = re.sub(r"/\*.*?\*/", "", open(MOE_HEADER).read(), flags=re.S)
     names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", src)
     assert set(names) == {"moe_ffn_fp8", "moe_ffn_fp8_workspace_bytes", "moe_ffn_fp8_workspace_offset", "moe_ffn_fp8_flops_per_pair",
-                          "moe_ffn_fp8_ex"}
+                          "moe_ffn_fp8_ex", "moe_ffn_fp8_row_tiles"}
     for name in names:
         assert hasattr(lib, name), name
     assert lib.moe_ffn_fp8_flops_per_pair(7168, 2048) == 6.0 * 7168 * 2048
+    # the row-tile rule: whole tiles and a remainder, one tile for an expert with up to 32 rows more than a tile
+    rt = lib.moe_ffn_fp8_row_tiles
+    rt.restype = ctypes.c_int
+    rt.argtypes = [ctypes.c_int, ctypes.c_int]
+    want128 = {0: 0, 1: 1, 64: 1, 128: 1, 129: 1, 160: 1, 161: 2, 256: 2, 257: 3, 288: 3, 289: 3, 700: 6}
+    assert {r: rt(r, 0) for r in want128} == want128 and {r: rt(r, 128) for r in want128} == want128
+    want64 = {0: 0, 64: 1, 65: 1, 96: 1, 97: 2, 128: 2, 129: 3, 700: 11}
+    assert {r: rt(r, 64) for r in want64} == want64
+    assert rt(-1, 0) == -1 and rt(10, 32) == -1 and rt(10, 256) == -1
+    for r in range(0, 2000, 7):                      # every row lands in exactly one tile of at most row_tile + 32 rows
+        for bm in (64, 128):
+            n = rt(r, bm)
+            assert (n == 0) == (r == 0) and (n - 1) * bm < r <= (n - 1) * bm + bm + 32 if n else True
 
 
 def test_moe_workspace_size_and_argument_errors(lib):

@@ -193,3 +193,31 @@ def test_moe_workspace_size_and_argument_errors(lib):
     assert m(x=A16 + 2) == -4 and m(ws=A16 + 16) == -4 and m(ids=A16 + 1) == -4
     ex = lambda a, b, rt=0: lib.moe_ffn_fp8_ex(A16, A16, A16, A16, A16, A16, A16, A16, 64, 256, 128, 4, 2, A16, 1 << 30, a, b, rt, None)
     assert ex(-1, 4) == -3 and ex(0, 5) == -3 and ex(3, 2) == -3 and ex(0, 4, 32) == -3 and ex(0, 4, 256) == -3
+
+
+# ---------------------------------------------------------------------------------------------
+# the headers are plain C: a C99 translation unit that includes all three and takes the address of
+# every entry point compiles without warnings and links against the library
+# ---------------------------------------------------------------------------------------------
+def test_headers_are_plain_c_and_link(tmp_path):
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    protos = {}
+    for h in ("attn.h", "gemm.h", "moe.h"):
+        src = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, h)).read(), flags=re.S)
+        protos[h] = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", src)
+    c = tmp_path / "use_abi.c"
+    lines = ['#include "attn.h"', '#include "gemm.h"', '#include "moe.h"', "#include <stdio.h>", "int main(void) {",
+             "    const void *fns[] = {"]
+    lines += ["        (const void *)%s," % name for h in protos for name in protos[h]]
+    lines += ["    };", '    printf("%d entry points, version %d, %s\\n", (int)(sizeof fns / sizeof fns[0]), attn_version(), attn_strerror(0));',
+              "    return gemm_bf16_flops(2, 3, 4) == 48.0 && moe_ffn_fp8_row_tiles(150, 0) == 1 ? 0 : 1;", "}"]
+    c.write_text("\n".join(lines) + "\n")
+    from paper_2604_18616_amd.build import LIB_PATH as lib
+    binding.load_library()                       # builds the library first if no built one exists
+    exe = str(tmp_path / "use_abi")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", inc, str(c), "-o", exe, lib,
+                           "-Wl,-rpath," + os.path.dirname(lib), "-Wl,-rpath,/opt/rocm/lib"])
+    res = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout
+    assert "entry points" in res.stdout and "success" in res.stdout

@@ -27,6 +27,13 @@ Two things make an end-to-end tolerance meaningless here, so the path is checked
   stage 3   the down-projection rows and y against the reference applied to THE KERNEL'S OWN
             intermediate codes: |o - ref| <= U(o); |y - ref| <= 2^-8 |ref| (the one bf16
             rounding) + sum_k |w_k| U(o_k)
+  end to end, from the inputs alone: stage 3 above feeds the kernel's codes to the reference's down
+            projection (as input, never as an expected value).  Independently of that, the reference
+            alone brackets y: every intermediate value lies within da of the reference's, so its
+            group scale and code lie in an interval (rounding is monotone), so does the dequantized
+            intermediate, and interval arithmetic through the down projection, U(o), the routing
+            weights and the one bf16 rounding gives [y_lo, y_hi], which must contain the kernel's y.
+            Most codes are pinned exactly; the few near a rounding boundary widen the bracket.
 plus an end-to-end sanity net on all tokens (row-wise relative L2 error, exact zeros).
 """
 import numpy as np
@@ -120,7 +127,8 @@ def check_slots(w, d, g, slots):
     rows = {}
     for t, k in slots:
         e, r = int(d["ids"][t, k]), int(g["pos"][t, k])
-        xd = VALS[g["xq"][t]] * np.repeat(g["xs"][t].astype(np.float64), 128)          # stage 1 has shown these exact
+        xf = I.bf16_bits_to_f32(d["x"][t])
+        xd = np.concatenate([VALS[c] * float(sc) for c, sc in (oracle.quant_group(xf[128 * b:128 * b + 128]) for b in range(w.H // 128))])
         w13d = dequant_weights(d["w13"][e], d["s13"][e])
         gu, dgu = w13d @ xd, mfma_uncertainty(xd, w13d)
         gate, up, dg, du = gu[:w.I], gu[w.I:], dgu[:w.I], dgu[w.I:]
@@ -145,13 +153,73 @@ def check_slots(w, d, g, slots):
         do = mfma_uncertainty(deq, dequant_weights(d["w2"][e], d["s2"][e]))
         if ((d["ids"][t] >= 0) & (d["ids"][t] < w.E)).sum() > 1:   # the fp32 row exists only for tokens with several local slots: a single one goes straight to y (check_y)
             assert np.all(np.abs(g["o"][r] - o_ref) <= do + 1e-30), ("down row", t, k, float((np.abs(g["o"][r] - o_ref) / do).max()))
-        rows[(t, k)] = (o_ref, do)
+        rows[(t, k)] = (o_ref, do, a, da)
     return rows
+
+
+GRID = np.unique(VALS[np.isfinite(VALS)])                 # the finite e4m3 values, ascending
+MID = 0.5 * (GRID[1:] + GRID[:-1])
+
+
+def bracket_y(w, d, t, rows):
+    """[y_lo, y_hi] for token t from the inputs and the reference alone (see the module docstring); rows: check_slots' result"""
+    y_lo, y_hi = np.zeros(w.H), np.zeros(w.H)
+    for k in range(w.KTOP):
+        if (t, k) not in rows:
+            continue
+        e = int(d["ids"][t, k])
+        a, da = rows[(t, k)][2], rows[(t, k)][3]
+        d_lo, d_hi = np.empty(w.I), np.empty(w.I)
+        for b in range(w.I // 128):
+            sl = slice(128 * b, 128 * b + 128)
+            lo, hi = a[sl] - da[sl], a[sl] + da[sl]
+            amax_lo = max(float(np.maximum(np.abs(a[sl]) - da[sl], 0.0).max()), 0.0)
+            amax_hi = float((np.abs(a[sl]) + da[sl]).max())
+            if amax_hi == 0.0:
+                s_lo = s_hi = 1.0
+            else:
+                s_lo, s_hi = amax_lo / 448.0 * (1 - 2e-6), amax_hi / 448.0 * (1 + 2e-6)
+                s_lo = max(s_lo, 1e-300)
+            v_lo = np.minimum(lo / s_lo, lo / s_hi)
+            v_hi = np.maximum(hi / s_lo, hi / s_hi)
+            v_lo = np.clip(v_lo - 2e-6 * np.abs(v_lo), -448, 448)
+            v_hi = np.clip(v_hi + 2e-6 * np.abs(v_hi), -448, 448)
+            c_lo = GRID[np.searchsorted(MID, v_lo, side="left")]       # rounding is monotone; ties resolved outwards
+            c_hi = GRID[np.searchsorted(MID, v_hi, side="right")]
+            d_lo[sl] = np.minimum(c_lo * s_lo, c_lo * s_hi)
+            d_hi[sl] = np.maximum(c_hi * s_lo, c_hi * s_hi)
+        w2d = dequant_weights(d["w2"][e], d["s2"][e])
+        wp, wn = np.maximum(w2d, 0.0), np.minimum(w2d, 0.0)
+        o_lo, o_hi = wp @ d_lo + wn @ d_hi, wp @ d_hi + wn @ d_lo
+        u = mfma_uncertainty(np.maximum(np.abs(d_lo), np.abs(d_hi)), w2d)
+        wt = float(d["wts"][t, k])
+        lo_k, hi_k = wt * (o_lo - u), wt * (o_hi + u)
+        y_lo += np.minimum(lo_k, hi_k)
+        y_hi += np.maximum(lo_k, hi_k)
+    r = 2.0 ** -8 * np.maximum(np.abs(y_lo), np.abs(y_hi)) + 1e-30
+    return y_lo - r, y_hi + r
+
+
+def check_y_from_inputs_alone(w, d, g, tokens, rows):
+    widths = []
+    for t in tokens:
+        if not any((t, k) in rows for k in range(w.KTOP)):
+            continue
+        y_lo, y_hi = bracket_y(w, d, t, rows)
+        y = g["y"][t]
+        assert np.all((y >= y_lo) & (y <= y_hi)), ("y outside the reference's bracket", t, float(np.max(np.maximum(y_lo - y, y - y_hi))))
+        ref = oracle.moe_ref(**d, rows=[t])[0]
+        assert np.all((ref >= y_lo) & (ref <= y_hi)), ("the reference's own y outside its bracket", t)
+        widths.append(float(np.median((y_hi - y_lo) / (np.abs(ref) + 1e-30))))
+    return widths
 
 
 def check_y(w, d, g, tokens):
     slots = [(t, k) for t in tokens for k in range(w.KTOP) if 0 <= d["ids"][t, k] < w.E]
     rows = check_slots(w, d, g, slots)
+    widths = check_y_from_inputs_alone(w, d, g, tokens, rows)
+    if widths:
+        print("y bracket from the inputs alone: median relative width %.3g (median over %d tokens)" % (float(np.median(widths)), len(widths)), flush=True)
     for t in tokens:
         y_ref, s_abs = np.zeros(w.H), np.zeros(w.H)
         for k in range(w.KTOP):

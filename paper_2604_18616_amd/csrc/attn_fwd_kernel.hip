@@ -86,7 +86,12 @@ __device__ __forceinline__ BlockCoord block_coord(int bid, int nblocks, int Hq, 
     const int logical = (bid < per_xcd * 8) ? (bid & 7) * per_xcd + (bid >> 3) : bid;
     const int W = g * nQt;
     const int pair = logical / W, rem = logical - pair * W;
-    const int ord = rem / g, hin = rem - ord * g;
+    int ord = rem / g;
+    const int hin = rem - ord * g;
+    // Causal tiles go heaviest first.  If one kv head's workgroups are more than an XCD's share (many query
+    // heads per kv head), a heavy-first order would give one XCD the long tiles and the next the short ones:
+    // then the order alternates longest, shortest, second longest, ... so that every stretch of it is balanced.
+    if (CAUSAL && W > per_xcd && per_xcd > 0) ord = (ord & 1) ? nQt - 1 - (ord >> 1) : (ord >> 1);
     BlockCoord c;
     c.b = pair / Hkv;
     c.hk = pair - c.b * Hkv;

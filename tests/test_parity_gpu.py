@@ -41,6 +41,9 @@ SMALL_CASES = [
     small("ragged_keys_causal_d64", 1, 4, 2, 513, 449, 64, True, 28),
     small("ragged_both_noncausal", 2, 3, 3, 1001, 1003, 128, False, 29),
     small("queries_65", 1, 2, 2, 65, 320, 128, True, 30),
+    # one kv head whose workgroups span several XCDs: the causal tile order alternates long and short tiles (5 and 6 tiles)
+    small("mqa16_causal_5_tiles", 1, 16, 1, 1280, 1280, 128, True, 31),
+    small("mqa16_causal_6_tiles_d64", 1, 16, 1, 1500, 1500, 64, True, 32),
 ]
 
 

@@ -50,6 +50,25 @@ __device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_o
                  :: "v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
 }
 
+// The same copy through a buffer resource: lane i's 16 bytes at (resource base + soff + voff) land at
+// lds_addr + 16*i, and a piece that lies past the resource's num_records arrives as zeros (the hardware's
+// out-of-range rule for buffer loads, checked on gfx950 with the LDS form of the instruction): the partial
+// last key tile needs no clamped addresses and no clearing afterwards.
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+__device__ __forceinline__ i32x4 buffer_resource(const void* base, unsigned bytes) {
+    const unsigned long long a = (unsigned long long)base;
+    i32x4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    r[1] = __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu));   // stride 0: a raw buffer
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);                              // num_records, in bytes
+    r[3] = 0x00020000;                                                              // 32-bit data format
+    return r;
+}
+__device__ __forceinline__ void dma_buf_to_lds_16B(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
+                 :: "v"(voff), "s"(rsrc), "s"(soff), "s"(lds_addr) : "memory");
+}
+
 // Exchange between lane l and lane l ^ 32.  v_permlane32_swap(a, b) returns
 //   r0 = { a[0..31], b[0..31] },  r1 = { a[32..63], b[32..63] }     (verified on gfx950),
 // so with b = a, (r0, r1) is (value held by the low-half lane, value held by the
@@ -296,7 +315,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
 
 
 // ------------------------------------------------------------------------------------
-// Ping-pong kernel (any Sk; RAGGED handles a partial last key tile).  512 threads = 8 wavefronts x 32 query rows
+// Ping-pong kernel (any Sk; RAGGED: a partial last key tile, copied through buffer resources that zero-fill past Sk).  512 threads = 8 wavefronts x 32 query rows
 // (Br = 256, as in the paper's Figure 1), Bc = 64.
 //
 // * K/V tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no staging
@@ -400,45 +419,33 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     // slot j >= NDMA part j - NDMA of K(t+1).  Issued spread over the phase: a burst from all
     // eight wavefronts right after the barrier queues 32 KB of requests in front of the
     // address unit and stalls the issuing wavefronts.
-    // RAGGED (Sk not a multiple of 64): the last key tile t_rag has rows past Sk.  Their source
-    // row is clamped to Sk-1 (the copy must stay inside the tensor); K rows past Sk are masked
-    // by the softmax, V rows past Sk are zeroed in LDS by the wavefront that copied them, after
-    // its copy has landed and before the barrier that publishes the tile (0 * garbage must be 0).
-    const int t_rag = RAGGED ? Sk / kBc : -1;
-    auto dma_part = [&](const __bf16* head, unsigned row_bytes, unsigned lane_off, int t, int buf, int n) __attribute__((always_inline)) {
+    // RAGGED (Sk not a multiple of 64): the last key tile has rows past Sk.  Its copies go through buffer
+    // resources that end with row Sk-1 of the head, so that the pieces past it arrive in LDS as zeros: no
+    // clamped addresses, nothing to clear afterwards (0 * garbage would not be 0), and the K columns past Sk
+    // are masked by the softmax like the causal ones.  Whole tiles keep the plain global copies, which measured
+    // 0.5-1 % faster.
+    i32x4 k_rsrc = {0, 0, 0, 0}, v_rsrc = {0, 0, 0, 0};
+    if constexpr (RAGGED) {   // a head's rows 0 .. Sk-1: row r starts at r * row_bytes and is D * 2 bytes long
+        k_rsrc = buffer_resource(kh, (unsigned)(Sk - 1) * k_rb + 2u * D);
+        v_rsrc = buffer_resource(vh, (unsigned)(Sk - 1) * v_rb + 2u * D);
+    }
+    auto dma_part = [&](auto is_k, const __bf16* head, unsigned row_bytes, unsigned lane_off, int t, int buf, int n) __attribute__((always_inline)) {
         const unsigned dst = lds_base + buf * TB + dma_dst_offset<D>(wave, n, 0);
         const unsigned tile_off = (unsigned)(t * kBc + n * 8 * ROWS_PER_DMA) * row_bytes;   // wavefront-uniform
-        if constexpr (RAGGED) {
-            if (t == t_rag) {
-                const int over = t * kBc + dma_row<D>(wave, n, lane) - (Sk - 1);
-                const unsigned off = tile_off + lane_off - (over > 0 ? (unsigned)over * row_bytes : 0u);
-                dma_to_lds_16B(head, off, dst);
-                return;
-            }
-        }
-        dma_to_lds_16B((const __bf16*)((const char*)head + tile_off), lane_off, dst);
-    };
-    auto zero_ragged_v = [&](int t) __attribute__((always_inline)) {
-        if constexpr (RAGGED) {
-            if (t == t_rag) {
-#pragma unroll
-                for (int n = 0; n < NDMA; ++n)
-                    if (t * kBc + dma_row<D>(wave, n, lane) >= Sk)
-                        *(u32x4*)(smem + (2 + (t & 1)) * TB + dma_dst_offset<D>(wave, n, lane)) = u32x4{0u, 0u, 0u, 0u};
-            }
-        }
+        if constexpr (RAGGED) dma_buf_to_lds_16B(decltype(is_k)::value ? k_rsrc : v_rsrc, lane_off, tile_off, dst);
+        else dma_to_lds_16B((const __bf16*)((const char*)head + tile_off), lane_off, dst);
     };
     auto issue_k = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
-        for (int n = 0; n < NDMA; ++n) dma_part(kh, k_rb, kgoff, t, t & 1, n);
+        for (int n = 0; n < NDMA; ++n) dma_part(IntC<1>{}, kh, k_rb, kgoff, t, t & 1, n);
     };
     auto issue_v = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
-        for (int n = 0; n < NDMA; ++n) dma_part(vh, v_rb, vgoff, t, 2 + (t & 1), n);
+        for (int n = 0; n < NDMA; ++n) dma_part(IntC<0>{}, vh, v_rb, vgoff, t, 2 + (t & 1), n);
     };
     auto dma_slot = [&](int t, int j) __attribute__((always_inline)) {
-        if (j < NDMA) { if (t < nT) dma_part(vh, v_rb, vgoff, t, 2 + (t & 1), j); }
-        else if (t + 1 < nT) dma_part(kh, k_rb, kgoff, t + 1, (t + 1) & 1, j - NDMA);
+        if (j < NDMA) { if (t < nT) dma_part(IntC<0>{}, vh, v_rb, vgoff, t, 2 + (t & 1), j); }
+        else if (t + 1 < nT) dma_part(IntC<1>{}, kh, k_rb, kgoff, t + 1, (t + 1) & 1, j - NDMA);
     };
     // vmcnt(0) only (expcnt/lgkmcnt fields left at their maxima).  The builtin, unlike
     // inline asm, also tells the compiler that its own earlier global loads have landed.
@@ -632,10 +639,9 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     // parity: t = 0 (QK only), 1 <= t < nTw (both), t = nTw (PV only), t > nTw (this
     // wavefront is past its causal limit and only keeps the barriers and its share of the
     // loads).  Every path executes 2 barriers per tile plus one at the end.
-    // close period t: own loads (V(t), K(t+1)) have landed, ragged V rows are cleared, publish
+    // close period t: own loads (V(t), K(t+1)) have landed, publish
     auto end_period = [&](int t) __attribute__((always_inline)) {
         wait_loads();
-        zero_ragged_v(t);
         phase_barrier();
     };
     auto loads = [&](int t) __attribute__((always_inline)) {

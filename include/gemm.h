@@ -47,9 +47,9 @@ int gemm_bf16(const void *a, const void *b, void *c, int M, int N, int K,
  * ("tile-size specialization" in the paper's Table 2): tile = 256 (256 x 256 tiles, one
  * workgroup per CU, two LDS stages 64 deep in k), 2564 (the same tile in four stages 32 deep),
  * 128 (128 x 128 tiles in two stages, two workgroups per CU), 1284 (128 x 128 tiles in four stages,
- * one per CU), 64 (64 x 64 tiles by two wavefronts, four stages), or 0 (what gemm_bf16 does: 256
- * when that yields at least 128 tiles; else 128 when that yields more than 256 tiles, 1284 when
- * more than 112, else 64).  Any other value: ATTN_ERR_UNSUPPORTED.  Shapes
+ * one per CU), 64 (64 x 64 tiles by two wavefronts, four stages), or 0 (what gemm_bf16 does: the shape
+ * with the best estimate of (throughput of the shape on a full chip) x (how full its last round of workgroups
+ * leaves the 256 CUs); see gemm_bf16_auto_tile).  Any other value: ATTN_ERR_UNSUPPORTED.  Shapes
  * that only the general kernel can take ignore the choice.  For tuning and for tests.
  */
 int gemm_bf16_tile(const void *a, const void *b, void *c, int M, int N, int K,

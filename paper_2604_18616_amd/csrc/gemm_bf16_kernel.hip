@@ -433,18 +433,27 @@ static void launch_tiled(GemmParams p, int b_is_nk, hipStream_t stream) {
 #undef GEMM_LAUNCH_TILED
 }
 
-// Tile-size choice by the number of tiles against the chip's 256 CUs (measured on square problems
-// from 1024 to 4096 in steps of 256-512, both layouts of B):
-//   256 x 256 tiles number at least 128             -> those (one workgroup per CU, best operand reuse);
-//   else 128 x 128 tiles number more than 256       -> those in two stages, two workgroups per CU;
-//   else they number more than 112                  -> those in four stages: one workgroup per CU, so the
-//                                                      depth of the copy pipeline has to come from one workgroup;
-//   else                                            -> 64 x 64 tiles: the time is the L2 -> LDS traffic of the
-//                                                      busiest CU, and four times the tiles spread it out.
+// Tile-size choice: the shape that promises the most throughput, estimated as (what the shape delivers when
+// every CU has its fill of workgroups) x (how full the last round of workgroups leaves the chip) x (the share of
+// the tiles' area that lies inside the result).  The first
+// factor is measured on large squares (TFLOP/s: 256 x 256 tiles 1330, 128 x 128 in two stages with two
+// workgroups per CU 1150, in four stages with one per CU 880, 64 x 64 with two per CU 700); the second is
+// tiles / (slots x rounds) with 256 CUs x workgroups per CU slots.  Checked against measurements on squares from
+// 1024 to 4096 and on rectangles from 1024 x 4096 to 1024 x 16384 and 3000 x 5000: it picks the fastest of the
+// four everywhere (a half-filled chip runs somewhat faster than the estimate, which never changed the order).
 int gemm_auto_tile(int M, int N) {
-    const long long large_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
-    const long long small_tiles = (long long)((M + 127) / 128) * ((N + 127) / 128);
-    return large_tiles >= 128 ? 256 : small_tiles > 256 ? 128 : small_tiles > 112 ? 1284 : 64;
+    struct Shape { int tile, edge, slots; double peak; };
+    static const Shape shapes[4] = {{256, 256, 256, 1330.0}, {128, 128, 512, 1150.0}, {1284, 128, 256, 880.0}, {64, 64, 512, 700.0}};
+    int best = 256;
+    double best_rate = -1.0;
+    for (const Shape& sh : shapes) {
+        const long long tiles = (long long)((M + sh.edge - 1) / sh.edge) * ((N + sh.edge - 1) / sh.edge);
+        const long long rounds = (tiles + sh.slots - 1) / sh.slots;
+        const double useful = (double)M * (double)N / ((double)tiles * sh.edge * sh.edge);   // edge tiles compute padding
+        const double rate = sh.peak * useful * (double)tiles / (double)(rounds * sh.slots);
+        if (rate > best_rate) { best_rate = rate; best = sh.tile; }
+    }
+    return best;
 }
 
 int gemm_launch(GemmParams p, int b_is_nk, bool tiled, int tile, hipStream_t stream) {

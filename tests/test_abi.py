@@ -125,7 +125,10 @@ def test_gemm_header_symbols_are_exported(lib):
     lib.gemm_bf16_auto_tile.argtypes = [ctypes.c_int, ctypes.c_int]
     want = {1024: 64, 1280: 64, 1536: 1284, 2048: 1284, 2304: 128, 2560: 128, 3072: 256, 4096: 256, 8192: 256, 16384: 256}
     assert {s: lib.gemm_bf16_auto_tile(s, s) for s in want} == want
-    assert lib.gemm_bf16_auto_tile(0, 8) == 0 and lib.gemm_bf16_auto_tile(64, 1 << 20) == 256
+    rect = {(1024, 8192): 128, (8192, 1024): 128, (2048, 4096): 128, (1024, 4096): 1284, (1536, 8192): 256, (3000, 5000): 256,
+            (1024, 16384): 256, (256, 16384): 1284, (128, 4096): 64, (64, 1 << 20): 64}
+    assert {mn: lib.gemm_bf16_auto_tile(*mn) for mn in rect} == rect
+    assert lib.gemm_bf16_auto_tile(0, 8) == 0
 
 
 def test_gemm_argument_errors_are_reported_without_a_gpu(lib):

@@ -31,7 +31,7 @@
  *                not be initialised and are garbage afterwards.  The library allocates nothing.
  * x, w13, w2, y, workspace must be 16-byte aligned; ids, wts, s13, s2 4-byte aligned.
  *
- * Supported: H, I multiples of 128, at most 8192; 1 <= E <= 256;
+ * Supported: H, I multiples of 128, at most 16384; 1 <= E <= 256;
  * 1 <= KTOP <= 16; 1 <= T, T*KTOP <= 2^20, T*H < 2^32 and T*KTOP*I < 2^32.  Inputs must be finite.
  *
  * `stream` is a hipStream_t passed as void* (NULL = the default stream): the call enqueues its

@@ -8,7 +8,7 @@
 
 static bool sizes_ok(int T, int H, int I, int E, int KTOP) {
     if (T <= 0 || H <= 0 || I <= 0 || E <= 0 || KTOP <= 0) return false;
-    if (H % 128 || I % 128 || H > 8192 || I > 8192) return false;
+    if (H % 128 || I % 128 || H > 16384 || I > 16384) return false;
     if (E > 256 || KTOP > 16) return false;
     if ((long long)T * KTOP > (1LL << 20)) return false;
     // 32-bit byte offsets of the tile copies: every activation matrix stays under 4 GiB

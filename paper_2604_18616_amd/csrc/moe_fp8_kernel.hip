@@ -209,7 +209,7 @@ __global__ __launch_bounds__(1024) void moe_prepare(MoeParams p, int stages) {
 constexpr int kMoeBN = 256;
 constexpr int kMoeLdsBytes = 3 * (160 * 128 + kMoeBN * 128);   // the largest stage set: three stages of BM = 160
 constexpr int kMoeSaBytes = 8 * 128;                          // row scales per stage: 8 row groups x 32 dwords
-constexpr int kMoeMaxKB = 64;                       // 128-blocks along k: H, I <= 8192
+constexpr int kMoeMaxKB = 128;                      // 128-blocks along k: H, I <= 16384
 
 typedef __attribute__((address_space(3))) char* LdsChar;      // LDS pointers stay typed as such: a generic pointer would
 typedef __attribute__((address_space(3))) float* LdsFloat;    // turn the scale reads into flat loads, which count as vector memory

@@ -191,7 +191,7 @@ def test_moe_workspace_size_and_argument_errors(lib):
 
     for name in ("x", "ids", "wts", "w13", "s13", "w2", "s2", "y", "ws"):
         assert m(**{name: None}) == -1, name
-    for kw in (dict(T=0), dict(H=100), dict(I=0), dict(E=0), dict(E=257), dict(K=17), dict(H=8192 + 128), dict(wsb=1024)):
+    for kw in (dict(T=0), dict(H=100), dict(I=0), dict(E=0), dict(E=257), dict(K=17), dict(H=16384 + 128), dict(wsb=1024)):
         assert m(**kw) == -2, kw
     assert m(x=A16 + 2) == -4 and m(ws=A16 + 16) == -4 and m(ids=A16 + 1) == -4
     ex = lambda a, b, rt=0: lib.moe_ffn_fp8_ex(A16, A16, A16, A16, A16, A16, A16, A16, 64, 256, 128, 4, 2, A16, 1 << 30, a, b, rt, None)

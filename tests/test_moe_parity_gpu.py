@@ -243,7 +243,9 @@ def sanity_net(y, ref, what):
 SMALL = [dict(T=12), dict(T=64, EP=1), dict(T=200, H=384, I=256, E=3, KTOP=3, EP=1), dict(T=70, H=128, I=128, E=2, KTOP=1, EP=1),
          dict(T=300, H=512, I=384, E=8, KTOP=4, EP=2), dict(T=1, H=256, I=128, E=4, KTOP=2, EP=1), dict(T=9, EP=16),
          dict(T=300, H=128, I=128, E=256, KTOP=16, EP=1),          # the largest expert and slot counts the library takes
-         dict(T=128, H=128, I=256, E=1, KTOP=1, EP=1)]              # one expert, exactly full row tiles
+         dict(T=128, H=128, I=256, E=1, KTOP=1, EP=1),              # one expert, exactly full row tiles
+         dict(T=40, H=256, I=16384, E=2, KTOP=1, EP=1),             # the longest reduction of the down product the library takes
+         dict(T=24, H=16384, I=128, E=2, KTOP=2, EP=1)]             # and of the gate/up product
 
 
 @pytest.mark.parametrize("row_tile", [64, 128])

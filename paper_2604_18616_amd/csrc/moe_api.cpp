@@ -78,6 +78,9 @@ extern "C" int moe_ffn_fp8_ex(const void* x, const int* ids, const float* wts,
     // runs the 64-, 128- or 160-row code that fits the rows it really has); `bm_override` is for tests
     p.bm = bm_override ? bm_override : 128;
     p.max_tiles = (int)(((size_t)T * KTOP + p.bm - 1) / p.bm + E);
+    // narrow column tiles of the down product are for problems whose wide tiles would not fill the chip: the grid is
+    // sized for them only if the upper bound on the row tiles is small enough for that to be possible
+    p.dn_narrow_ok = (long long)p.max_tiles * ((H + 255) / 256) < 4096 ? 1 : 0;
     p.offsets = (int*)(ws + off[0]); p.cursor = (int*)(ws + off[1]); p.ntiles = (int*)(ws + off[2]);
     p.tile_rec = (MoeTileRec*)(ws + off[3]);
     p.sorted_tok = (int*)(ws + off[6]); p.pos = (int*)(ws + off[7]);

@@ -213,17 +213,20 @@ constexpr int kMoeMaxKB = 128;                      // 128-blocks along k: H, I 
 
 typedef __attribute__((address_space(3))) char* LdsChar;      // LDS pointers stay typed as such: a generic pointer would
 typedef __attribute__((address_space(3))) float* LdsFloat;    // turn the scale reads into flat loads, which count as vector memory
-template <bool UP, int BM>
+template <bool UP, int BM, int BN>
 __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row0, int rows, int nt, LdsChar smem, LdsFloat sa_stage, LdsFloat sb_tab) {
+    static_assert(BN == 256 || (BN == 128 && !UP), "the gate/up product pairs two 32-row weight blocks per wavefront");
     constexpr int NS = 3;                           // LDS stages
-    constexpr int kStageA = BM * 128, kStageB = kMoeBN * 128, kStage = kStageA + kStageB;
+    constexpr int NIN = BN / 128;                   // 32-row weight blocks per wavefront (wavefront wn: weight rows 32 NIN wn ..)
+    constexpr int NCB = BN / 32;                    // copy instructions of the weights per copying wavefront and stage
+    constexpr int kStageA = BM * 128, kStageB = BN * 128, kStage = kStageA + kStageB;
     static_assert(NS * kStage <= kMoeLdsBytes, "stages exceed the workgroup's LDS");
     constexpr int NCA = BM / 32;                    // copy instructions of the routed rows per copying wavefront and stage
     constexpr int kW0 = BM == 160 ? 96 : BM / 2;    // routed rows of the wavefronts wm = 0; wm = 1 takes the rest
     constexpr int MB = BM == 160 ? 3 : BM / 64;     // 32-row blocks of routed rows per wavefront (BM = 160: the third only for wm = 0)
     constexpr int RPW = BM / 8;                     // routed rows per row group: a group's scales are one dword copy per stage
     static_assert(RPW <= 32, "a row group's scales fill at most the 32 dwords of its slot");
-    constexpr int kCopies = NCA + 8 + 2;            // vmem operations per copying wavefront and stage
+    constexpr int kCopies = NCA + NCB + 2;          // vmem operations per copying wavefront and stage
     // s_waitcnt immediate for vmcnt((NS - 2) kCopies), lgkmcnt(0): vmcnt's low four bits, then its two high bits at 14
     constexpr int kLater = (NS - 2) * kCopies;
     constexpr int kWaitNext = 0x0070 | (kLater & 15) | ((kLater >> 4) << 14);
@@ -240,14 +243,14 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
 
     // ---- copies: wavefronts 0-3 (one per SIMD) issue them: per stage instructions c + 4 n of the
-    // routed rows (n < NCA) and of the weights (n < 8), and the dword copies of the row scales for
+    // routed rows (n < NCA) and of the weights (n < NCB), and the dword copies of the row scales for
     // the row groups c and c + 4.  Wavefronts 4-7 issue no memory traffic in the loop: four issuers
     // measured 5-10 % faster than eight.  (An L2 warm-up by the idle wavefronts, as in the bf16 GEMM,
     // was tried and is harmful here: an XCD's L2 holds 128 KB per CU, less than the LDS stages
     // already in flight, so lines touched early are evicted before the copies ask for them.) ----
     const bool copier = wave < 4;
     const int c4 = wave & 3;
-    unsigned a_off[NCA], b_off[8], s_off[2];
+    unsigned a_off[NCA], b_off[NCB], s_off[2];
     {
 #pragma unroll
         for (int n = 0; n < NCA; ++n) {
@@ -257,11 +260,11 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row
             a_off[n] = (unsigned)src * (unsigned)KB + 16u * (unsigned)kt_dma_chunk(i, lane);
         }
 #pragma unroll
-        for (int n = 0; n < 8; ++n) {
+        for (int n = 0; n < NCB; ++n) {
             const int i = c4 + 4 * n, tr = kt_dma_row(i, lane);
             int wrow;
             if (UP) wrow = ((tr & 63) >> 5) * p.I + nt * 128 + ((tr >> 6) << 5) + (tr & 31);
-            else wrow = min(nt * kMoeBN + tr, p.H - 1);               // rows past H re-read the last one
+            else wrow = min(nt * BN + tr, p.H - 1);                   // rows past H re-read the last one
             b_off[n] = (unsigned)wrow * (unsigned)KB + 16u * (unsigned)kt_dma_chunk(i, lane);
         }
 #pragma unroll
@@ -282,7 +285,7 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row
         static_for<0, NCA>([&](auto n) __attribute__((always_inline)) {
             dma_to_lds_16B<s * kStage + n.value * 4096>(a_base + (size_t)U * 128, a_off[n.value], lds_copy_base);
         });
-        static_for<0, 8>([&](auto n) __attribute__((always_inline)) {
+        static_for<0, NCB>([&](auto n) __attribute__((always_inline)) {
             dma_to_lds_16B<s * kStage + kStageA + n.value * 4096>(b_base + (size_t)U * 128, b_off[n.value], lds_copy_base);
         });
         if (lane < 32) {                            // a slot holds 32 dwords: the upper half of the wavefront stays out
@@ -297,10 +300,10 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row
         const int which = tid / nK, b = tid - which * nK;
         const float* src;
         if (UP) src = p.s13 + ((size_t)e * 2 * (p.I >> 7) + (which ? (p.I >> 7) : 0) + nt) * nK;   // gate rows, up rows of block nt
-        else src = p.s2 + ((size_t)e * (p.H >> 7) + min(nt * 2 + which, (p.H >> 7) - 1)) * nK;
+        else src = p.s2 + ((size_t)e * (p.H >> 7) + min(nt * NIN + (NIN == 2 ? which : 0), (p.H >> 7) - 1)) * nK;
         sb_tab[which * kMoeMaxKB + b] = src[b];
     }
-    const int sb_sel0 = UP ? 0 : (wn >> 1), sb_sel1 = UP ? 1 : (wn >> 1);
+    const int sb_sel0 = UP ? 0 : (NIN == 2 ? wn >> 1 : 0), sb_sel1 = UP ? 1 : sb_sel0;
 
     // ---- per-lane LDS read addresses (stage 0): K = 64 operand = 32 bytes = chunks 4 ks + 2 half + {0,1} ----
     unsigned a_addr[2][2], b_addr[2][2];
@@ -309,7 +312,7 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             a_addr[ks][q] = lds_base + kt_offset(kW0 * wm + (lane & 31), 4 * ks + 2 * half + q);
-            b_addr[ks][q] = lds_base + kStageA + kt_offset(64 * wn + (lane & 31), 4 * ks + 2 * half + q);
+            b_addr[ks][q] = lds_base + kStageA + kt_offset(32 * NIN * wn + (lane & 31), 4 * ks + 2 * half + q);
         }
     // row scale of routed row m of the tile: dword m % RPW of row group m / RPW
     int sa_idx[MB];
@@ -324,9 +327,9 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
-    f32x16 acc[2][MB];
+    f32x16 acc[NIN][MB];
 #pragma unroll
-    for (int in = 0; in < 2; ++in)
+    for (int in = 0; in < NIN; ++in)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -376,8 +379,8 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row
         if (copier && U + NS - 1 < nK) dma_stage(U + NS - 1, IntC<(s + NS - 1) % NS>{});
         const float sb0 = sb_tab[sb_sel0 * kMoeMaxKB + U], sb1 = sb_tab[sb_sel1 * kMoeMaxKB + U];
         const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-        i32x8 fb[2][2];
-        static_for<0, 2>([&](auto in) __attribute__((always_inline)) {
+        i32x8 fb[NIN][2];
+        static_for<0, NIN>([&](auto in) __attribute__((always_inline)) {
             fb[in.value][0] = frag(b_addr[0][0], b_addr[0][1], s * kStage + in.value * 4096);
             fb[in.value][1] = frag(b_addr[1][0], b_addr[1][1], s * kStage + in.value * 4096);
         });
@@ -386,7 +389,7 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row
             const float sa = sa_stage[s * (kSaBytes / 4) + sa_idx[mb.value]];
             const i32x8 fa0 = frag(a_addr[0][0], a_addr[0][1], s * kStage + mb.value * 4096);
             const i32x8 fa1 = frag(a_addr[1][0], a_addr[1][1], s * kStage + mb.value * 4096);
-            static_for<0, 2>([&](auto in) __attribute__((always_inline)) {
+            static_for<0, NIN>([&](auto in) __attribute__((always_inline)) {
                 f32x16 part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[in.value][0], fa0, zero, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
                 part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[in.value][1], fa1, part, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
                 const float f = sa * (in.value == 0 ? sb0 : sb1);
@@ -462,10 +465,10 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row
                 const int dst = __float_as_int(hand[2 * m]);
                 const float w = hand[2 * m + 1];
 #pragma unroll
-                for (int in = 0; in < 2; ++in)
+                for (int in = 0; in < NIN; ++in)
 #pragma unroll
                     for (int g4 = 0; g4 < 4; ++g4) {
-                        const int c = nt * kMoeBN + 64 * wn + 32 * in + 8 * g4 + 4 * half;
+                        const int c = nt * BN + 32 * NIN * wn + 32 * in + 8 * g4 + 4 * half;
                         if (c < p.H) {
                             const f32x4 v = {acc[in][mb][4 * g4], acc[in][mb][4 * g4 + 1], acc[in][mb][4 * g4 + 2], acc[in][mb][4 * g4 + 3]};
                             if (dst >= 0) {
@@ -496,8 +499,15 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     // expert; inside an expert column tile by column tile, the expert's row tiles innermost: neighbours
     // share their weight tile (same nt) or their routed rows (same mt), which the XCD's L2 then
     // fetches once.
-    const int NT = UP ? (p.I >> 7) : (p.H + kMoeBN - 1) / kMoeBN;
-    const int live = p.ntiles[0] * NT, per_xcd = (live + 7) >> 3;
+    // Down product: column tiles of 256 weight rows, or of 128 when the wide ones would not give every CU a
+    // workgroup (few experts in use, or a small H: 8 experts of 4096 x 14336 make 128 wide tiles).  The host
+    // sizes the grid for the narrow tiles when the problem is small enough for that to happen (p.dn_narrow_ok);
+    // the choice itself needs the number of row tiles, known only here.  (With enough wide tiles the narrow ones
+    // are 3-15 % slower: measured.)
+    const int ntl = p.ntiles[0];
+    const bool narrow = !UP && p.dn_narrow_ok && ntl * ((p.H + kMoeBN - 1) / kMoeBN) < 256;
+    const int NT = UP ? (p.I >> 7) : narrow ? (p.H >> 7) : (p.H + kMoeBN - 1) / kMoeBN;
+    const int live = ntl * NT, per_xcd = (live + 7) >> 3;
     const int bid = blockIdx.x;
     const int logical = (bid & 7) * per_xcd + (bid >> 3);
     if ((bid >> 3) >= per_xcd || logical >= live) return;   // uniform: before any barrier
@@ -509,9 +519,17 @@ __global__ __launch_bounds__(512, 1) void moe_gemm(MoeParams p) {
     const int rows = j == cnt - 1 ? rec.rows - j * p.bm : p.bm;   // uniform
     const LdsChar tiles = LDS_PTR(char, smem);
     const LdsFloat sa = LDS_PTR(float, sa_stage), sb = LDS_PTR(float, sb_tab);
-    if (rows > 128) moe_gemm_tile<UP, 160>(p, e, row0, rows, nt, tiles, sa, sb);
-    else if (rows > 64) moe_gemm_tile<UP, 128>(p, e, row0, rows, nt, tiles, sa, sb);
-    else moe_gemm_tile<UP, 64>(p, e, row0, rows, nt, tiles, sa, sb);
+    if constexpr (!UP) {
+        if (narrow) {
+            if (rows > 128) moe_gemm_tile<false, 160, 128>(p, e, row0, rows, nt, tiles, sa, sb);
+            else if (rows > 64) moe_gemm_tile<false, 128, 128>(p, e, row0, rows, nt, tiles, sa, sb);
+            else moe_gemm_tile<false, 64, 128>(p, e, row0, rows, nt, tiles, sa, sb);
+            return;
+        }
+    }
+    if (rows > 128) moe_gemm_tile<UP, 160, 256>(p, e, row0, rows, nt, tiles, sa, sb);
+    else if (rows > 64) moe_gemm_tile<UP, 128, 256>(p, e, row0, rows, nt, tiles, sa, sb);
+    else moe_gemm_tile<UP, 64, 256>(p, e, row0, rows, nt, tiles, sa, sb);
 }
 
 // ------------------------------------------------------------------------------------
@@ -551,7 +569,8 @@ int moe_launch(const MoeParams& p, int first, int last, hipStream_t stream) {
         hipLaunchKernelGGL(moe_prepare, dim3(1 + (on(1) ? (unsigned)((items + 31) / 32) : 0u)), dim3(1024), 0, stream, p,
                            (on(0) ? 1 : 0) | (on(1) ? 2 : 0));
     auto grid8 = [](long long n) { return dim3((unsigned)((n + 7) / 8 * 8)); };   // the tile order wants a multiple of 8
-    const dim3 g_up = grid8((long long)p.max_tiles * (p.I / 128)), g_dn = grid8((long long)p.max_tiles * ((p.H + kMoeBN - 1) / kMoeBN));
+    const dim3 g_up = grid8((long long)p.max_tiles * (p.I / 128)),
+               g_dn = grid8((long long)p.max_tiles * (p.dn_narrow_ok ? p.H / 128 : (p.H + kMoeBN - 1) / kMoeBN));
     if (on(2)) hipLaunchKernelGGL((moe_gemm<true>), g_up, dim3(512), 0, stream, p);
     if (on(3)) hipLaunchKernelGGL((moe_gemm<false>), g_dn, dim3(512), 0, stream, p);
     if (on(4)) hipLaunchKernelGGL(moe_combine, dim3((unsigned)(((p.H / 8 + 255) / 256) * p.T)), dim3(256), 0, stream, p);

@@ -35,6 +35,7 @@ struct MoeParams {
     int T, H, I, E, KTOP;
     int bm;                   // rows per tile for this call: 64 or 128
     int max_tiles;            // upper bound on the number of row tiles: ceil(T*KTOP / bm) + E
+    int dn_narrow_ok;         // the grid of the down product is sized for 128-row column tiles (the kernel decides whether to use them)
     // workspace carve-up (all device pointers into the caller's workspace)
     int* offsets;             // [E + 1] first sorted row of each expert
     int* cursor;              // [E]     scatter cursors

@@ -6,18 +6,19 @@
 //
 // Five stages in four kernels on one stream, all state in the caller's workspace:
 //   moe_prepare   workgroup 0: counting sort of the local (token, slot) pairs by expert (sorted
-//                 rows, the inverse map, the list of row tiles (expert, first row, rows)); the
-//                 other workgroups: activation quantization, one group of 128 features per 32 lanes;
+//                 rows, the inverse map, one record per row tile); the other workgroups: activation
+//                 quantization, eight groups of 128 features per 32 lanes;
 //   moe_gemm<UP>  per (row tile, 128 intermediate columns): gate and up products on
 //                 v_mfma_scale_f32_32x32x64_f8f6f4, block scales applied per 128-deep stage,
 //                 SiLU gate, requantization of the 128-column group, FP8 store;
-//   moe_gemm<DN>  per (row tile, 256 output columns): down product; the row of a token with a single local slot
+//   moe_gemm<DN>  per (row tile, 256 output columns, or 128 if that is what it takes to give every CU a
+//                 workgroup): down product; the row of a token with a single local slot
 //                 goes straight to y (weight * row, rounded once), the others as fp32 rows to the workspace;
 //   moe_combine   y[t] = sum over local slots of weight * row, rounded once to bf16, for the tokens with
 //                 two or more local slots; zeros for those with none.
 // With 16 to 256 rows per expert the products are bound by streaming the expert weights from
-// HBM (each byte is used for 2 x rows FLOPs), so the grouped product keeps three 40-48 KB stages
-// of direct-to-LDS copies in flight per workgroup and does nothing clever with the MFMAs.
+// HBM (each byte is used for 2 x rows FLOPs), so the grouped product keeps three 40-52 KB stages
+// of direct-to-LDS copies per workgroup, two of them in flight, and does nothing clever with the MFMAs.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

@@ -96,18 +96,42 @@ def vendor_time_ms(torch, fn, n=30):
     return e0.elapsed_time(e1) / n
 
 
-def mfma_sustained_tflops(torch, lib, dev, stream):
-    """What this GPU sustains on nothing but bf16 MFMAs (same stream, HIP events)."""
+def mfma_sustained_tflops(torch, lib, dev, stream, data=0):
+    """What this GPU sustains on nothing but bf16 MFMAs (same stream, HIP events), ~40 ms per measurement so that
+    the power controller settles.  data: 0 smoothly varying operands, 1 zeros, 2 normal-like values, 3 those on the
+    16x16x32 instruction (everything else, and every kernel of the library, uses 32x32x16)."""
     sink = torch.zeros(16, dtype=torch.float32, device=dev)
-    blocks, iters, sp = prop_cus(torch, dev), 20000, stream.cuda_stream
-    lib.attn_mfma_calibration(sink.data_ptr(), blocks, 2000, sp)
+    blocks, sp = prop_cus(torch, dev), stream.cuda_stream
+    iters = 300000 if data == 0 else 150000
+    lib.attn_mfma_calibration_data(sink.data_ptr(), blocks, 2000, data, sp)
     torch.cuda.synchronize()
     c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     c0.record(stream)
-    flops = lib.attn_mfma_calibration(sink.data_ptr(), blocks, iters, sp)
+    flops = lib.attn_mfma_calibration_data(sink.data_ptr(), blocks, iters, data, sp)
     c1.record(stream)
     torch.cuda.synchronize()
     return flops / (c0.elapsed_time(c1) * 1e-3) / 1e12 if flops > 0 else None
+
+
+def mfma_sustained_by_operands(torch, lib, dev, stream):
+    """The matrix pipe alone against the power limit: its sustained rate depends on the operand data."""
+    return {"zeros": mfma_sustained_tflops(torch, lib, dev, stream, 1),
+            "smooth": mfma_sustained_tflops(torch, lib, dev, stream, 0),
+            "normal": mfma_sustained_tflops(torch, lib, dev, stream, 2),
+            "normal_16x16x32": mfma_sustained_tflops(torch, lib, dev, stream, 3)}
+
+
+INPUT_KINDS = {"normal": "synthetic",
+               "zeros": "synthetic, all zeros (power-limit context: NOT the benchmark inputs)",
+               "const": "synthetic, one constant per tensor (power-limit context: NOT the benchmark inputs)"}
+
+
+def override_inputs(kind, arrays, I):
+    """--inputs zeros / const: overwrite the seeded bf16 bit patterns in place (0, or 0.5 / 0.25 / 1.0 in turn)."""
+    if kind == "normal":
+        return
+    for arr, c in zip(arrays, (0.5, 0.25, 1.0)):
+        arr[...] = 0 if kind == "zeros" else I.f32_to_bf16_bits(np.full(1, c, dtype=np.float32))[0]
 
 
 GEMM_CPU_SAMPLES = 1 << 17     # sampled outputs for the CPU leg of a GEMM workload
@@ -116,6 +140,7 @@ GEMM_CPU_SAMPLES = 1 << 17     # sampled outputs for the CPU leg of a GEMM workl
 def bench_gemm(args, torch, lib, binding, I, dev) -> int:
     w = I.GEMM_WORKLOADS[args.workload]
     ab, bb = I.make_ab(w)
+    override_inputs(args.inputs, (ab, bb), I)
     to_dev = lambda x: torch.from_numpy(x.view(np.int16)).view(torch.bfloat16).to(dev)
     a, b = to_dev(ab), to_dev(bb)
     c = torch.full((w.M, w.N), float("nan"), dtype=torch.bfloat16, device=dev)
@@ -130,7 +155,8 @@ def bench_gemm(args, torch, lib, binding, I, dev) -> int:
 
     ms_per_step, kernel_ms = time_steps(torch, step, stream, args.steps, args.warmup)
     stats = launch_stats(torch, step, stream)
-    sustained = mfma_sustained_tflops(torch, lib, dev, stream)
+    by_operands = mfma_sustained_by_operands(torch, lib, dev, stream)
+    sustained = by_operands["normal"]          # the benchmark inputs are normal-distributed
     flops = lib.gemm_bf16_flops(w.M, w.N, w.K)
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kernel_ms * 1e-3) / 1e12
@@ -153,7 +179,7 @@ def bench_gemm(args, torch, lib, binding, I, dev) -> int:
         got = I.bf16_bits_to_f32(c.view(-1)[idx].view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
         err = np.abs(got - ref)
         tol = 2.0 ** -8 * np.abs(ref) + (w.K / 16 + 4) * 2.0 ** -23 * sabs
-        parity = {"max_abs": float(err.max()), "max_err_over_tol": float((err / tol).max()), "outputs_checked": int(n),
+        parity = {"max_abs": float(err.max()), "max_err_over_tol": float(np.divide(err, tol, out=np.zeros_like(err), where=tol > 0).max()), "outputs_checked": int(n),
                   "ok": bool(np.isfinite(got).all() and (err <= tol).all())}
         cpu = {"value": 2.0 * w.K * n / cpu_s / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
                "sample": "%d seeded output elements of %s, %.1f s" % (n, w.name, cpu_s)}
@@ -163,7 +189,7 @@ def bench_gemm(args, torch, lib, binding, I, dev) -> int:
         "metric": "bf16 GEMM TFLOP/s and % of MI355X bf16 MFMA peak",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": INPUT_KINDS[args.inputs],
         "config": {"workload": "%s: M=%d N=%d K=%d, B stored %s, N(0,1) entries, seed %d"
                                % (w.name, w.M, w.N, w.K, "[N,K]" if w.b_is_nk else "[K,N]", w.seed),
                    "flops_per_step": flops, "flop_convention": "2*M*N*K"},
@@ -171,6 +197,7 @@ def bench_gemm(args, torch, lib, binding, I, dev) -> int:
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": read_traffic(w.name, "gemm_bf16"),
                      "kernel_ms": kernel_ms, "kernel_ms_single_launches": stats, "mfma_sustained_tflops": sustained,
+                     "mfma_sustained_by_operands": by_operands,
                      "frac_of_sustained": (achieved / sustained) if sustained else None},
         "cpu_baseline": cpu,
         "parity": parity,
@@ -268,6 +295,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C3",
                     help="attention: C1..C5 (C3 = the headline config), N8K, P1024..P16384 (the paper's shape); "
                          "bf16 GEMM: G1024..G16384, with a trailing T for B stored [N,K]; fused MoE FP8: M1024..M16384")
+    ap.add_argument("--inputs", default="normal", choices=sorted(INPUT_KINDS),
+                    help="attention and GEMM only: 'normal' = the seeded benchmark inputs (default, the only ones `value` is "
+                         "quoted on); 'zeros' / 'const' show what the same kernel does when the power limit is out of the way")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU reference leg (profiling runs)")
     ap.add_argument("--vendor-context", action="store_true",
                     help="also time the library PyTorch ships for the same operation on the same inputs (torch.matmul / "
@@ -308,6 +338,7 @@ def main() -> int:
         return bench_moe(args, torch, lib, binding, I, dev)
     w = I.WORKLOADS[args.workload]
     qb, kb, vb = I.make_qkv(w)
+    override_inputs(args.inputs, (qb, kb, vb), I)
     to_dev = lambda a: torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
     q, k, v = to_dev(qb), to_dev(kb), to_dev(vb)
     o = torch.full(q.shape, float("nan"), dtype=torch.bfloat16, device=dev)
@@ -327,7 +358,8 @@ def main() -> int:
     # stream give the average kernel duration used for the roofline figure
     ms_per_step, kernel_ms = time_steps(torch, step, stream, args.steps, args.warmup)
     stats = launch_stats(torch, step, stream)
-    mfma_sustained = mfma_sustained_tflops(torch, lib, dev, stream)
+    by_operands = mfma_sustained_by_operands(torch, lib, dev, stream)
+    mfma_sustained = by_operands["normal"]     # the benchmark inputs are normal-distributed
 
     flops = lib.attn_fwd_flops(*dims, causal)
     value = flops / (ms_per_step * 1e-3) / 1e12
@@ -376,7 +408,7 @@ def main() -> int:
         "metric": "attention fwd TFLOP/s (bf16) and % of MI355X bf16 MFMA peak",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": INPUT_KINDS[args.inputs],
         "config": {"workload": "%s: B=%d Hq=%d Hkv=%d Sq=%d Sk=%d D=%d %s, scale=1/sqrt(D), seed %d"
                                % (w.name, w.B, w.Hq, w.Hkv, w.Sq, w.Sk, w.D, "causal" if w.causal else "non-causal", w.seed),
                    "flops_per_step": flops, "flop_convention": "algorithmic: 4*D per visible (query,key) pair"},
@@ -385,6 +417,7 @@ def main() -> int:
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": read_traffic(w.name),
                      "kernel_ms": kernel_ms, "kernel_ms_single_launches": stats, "mfma_sustained_tflops": mfma_sustained,
+                     "mfma_sustained_by_operands": by_operands,
                      "frac_of_sustained": (achieved / mfma_sustained) if mfma_sustained else None},
         "cpu_baseline": cpu,
         "parity": parity,

@@ -104,6 +104,18 @@ double attn_fwd_flops(int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal)
  */
 double attn_mfma_calibration(float *sink, int blocks, int iters, void *stream);
 
+/*
+ * The same measurement with operands of a chosen kind.  The GPU runs against a power limit and the clock it
+ * settles to under matrix load depends on how many operand bits toggle, so the rate the matrix pipe sustains is a
+ * function of the data: data 0 = the smoothly varying positive operands of attn_mfma_calibration, 1 = all zeros
+ * (what the pipe does when power is no limit), 2 = values with the spread of a standard normal, different per
+ * lane, element and workgroup (the distribution of the benchmark inputs), 3 = the operands of 2 on the other
+ * bf16 shape, v_mfma_f32_16x16x32_bf16 (every other kind and every kernel here use 32x32x16).  Kinds 1 and 2
+ * issue 8*iters MFMAs per wavefront, kind 3 16*iters of the half-sized instruction: the same FLOPs, which the
+ * return value counts.  Same error behaviour; any other `data` returns -1.0.
+ */
+double attn_mfma_calibration_data(float *sink, int blocks, int iters, int data, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

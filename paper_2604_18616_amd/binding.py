@@ -62,6 +62,8 @@ def load_library(build_if_missing: bool = True):
         lib.attn_fwd_flops.argtypes = [i, i, i, i, i, i, i]
         lib.attn_mfma_calibration.restype = ctypes.c_double
         lib.attn_mfma_calibration.argtypes = [p, i, i, p]
+        lib.attn_mfma_calibration_data.restype = ctypes.c_double
+        lib.attn_mfma_calibration_data.argtypes = [p, i, i, i, p]
         _lib = lib
     return _lib
 

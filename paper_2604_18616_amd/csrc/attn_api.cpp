@@ -71,7 +71,12 @@ extern "C" int attn_fwd_strided(const void* q, const void* k, const void* v, voi
 
 extern "C" double attn_mfma_calibration(float* sink, int blocks, int iters, void* stream) {
     if (!sink || blocks <= 0 || iters <= 0) return -1.0;
-    return attn_launch_mfma_calibration(sink, blocks, iters, (hipStream_t)stream);
+    return attn_launch_mfma_calibration(sink, blocks, iters, 0, (hipStream_t)stream);
+}
+
+extern "C" double attn_mfma_calibration_data(float* sink, int blocks, int iters, int data, void* stream) {
+    if (!sink || blocks <= 0 || iters <= 0 || data < 0 || data > 3) return -1.0;
+    return attn_launch_mfma_calibration(sink, blocks, iters, data, (hipStream_t)stream);
 }
 
 extern "C" const char* attn_strerror(int code) {

@@ -770,12 +770,65 @@ __global__ __launch_bounds__(512, 1) void mfma_calibration_kernel(float* sink, i
     if (t == 123456.789f) sink[0] = t;      // keeps the accumulators alive; never true in practice
 }
 
+// The same with operands of a chosen kind: the GPU runs against a power limit, and what the matrix pipe sustains
+// depends on how many operand bits toggle.  data 1: all zeros; data 2: values with the spread of a standard normal
+// (sums of four uniform hashes, scaled), different per lane, element and workgroup, eight operand pairs in rotation;
+// data 3: those on the 16x16x32 shape.
+__device__ __forceinline__ float calibration_normal(unsigned x) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { x = x * 1664525u + 1013904223u; s += (float)(x >> 8) * (1.0f / 16777216.0f); }
+    return (s - 2.0f) * 1.7f;
+}
+// data 3: the normal-like operands on the other bf16 shape, v_mfma_f32_16x16x32_bf16 (same FLOPs per iteration in
+// twice the instructions, a quarter of the accumulator registers each).
+template <bool SHAPE16>
+__global__ __launch_bounds__(512, 1) void mfma_calibration_data_kernel(float* sink, int iters, int data) {
+    bf16x8 a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const unsigned id = ((blockIdx.x * 512u + threadIdx.x) * 8u + i) * 8u + e;
+            a[i][e] = (__bf16)(data >= 2 ? calibration_normal(id) : 0.f);
+            b[i][e] = (__bf16)(data >= 2 ? calibration_normal(id ^ 0x9E3779B9u) : 0.f);
+        }
+    float t = 0.f;
+    if constexpr (SHAPE16) {
+        typedef __attribute__((ext_vector_type(4))) float f32x4;
+        f32x4 c[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c[i] = f32x4{0};
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int m = 0; m < 16; ++m) c[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m & 7], b[(m * 3 + 1) & 7], c[m], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) t += (c[i][0] + c[i][1]) + (c[i][2] + c[i][3]);
+    } else {
+        f32x16 c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c[i] = f32x16{0};
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int m = 0; m < 8; ++m) c[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[(m * 3 + 1) & 7], c[m], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t += c[i][r];
+    }
+    if (t == 123456.789f) sink[0] = t;
+}
+
 }  // namespace
 
-double attn_launch_mfma_calibration(float* sink, int blocks, int iters, hipStream_t stream) {
-    hipLaunchKernelGGL(mfma_calibration_kernel, dim3((unsigned)blocks), dim3(512), 0, stream, sink, iters);
+double attn_launch_mfma_calibration(float* sink, int blocks, int iters, int data, hipStream_t stream) {
+    if (data == 0) hipLaunchKernelGGL(mfma_calibration_kernel, dim3((unsigned)blocks), dim3(512), 0, stream, sink, iters);
+    else if (data == 3) hipLaunchKernelGGL(mfma_calibration_data_kernel<true>, dim3((unsigned)blocks), dim3(512), 0, stream, sink, iters, data);
+    else hipLaunchKernelGGL(mfma_calibration_data_kernel<false>, dim3((unsigned)blocks), dim3(512), 0, stream, sink, iters, data);
     if (hipGetLastError() != hipSuccess) return -1.0;
-    return (double)blocks * 8.0 * (double)iters * 4.0 * 32768.0;   // 2*32*32*16 flop per MFMA
+    return (double)blocks * 8.0 * (double)iters * (data == 0 ? 4.0 : 8.0) * 32768.0;   // 2*32*32*16 flop per MFMA
 }
 
 // Host-side launcher: the only symbol the C-ABI translation unit needs from this file.

@@ -24,4 +24,4 @@ int attn_launch(AttnParams p, int D, int causal, hipStream_t stream);
 
 // Enqueue the pure-MFMA calibration kernel (blocks x 8 wavefronts x iters x 4 MFMAs); returns
 // the FLOPs it performs, or -1 if the launch was refused.  sink: >= 4 bytes of device memory.
-double attn_launch_mfma_calibration(float* sink, int blocks, int iters, hipStream_t stream);
+double attn_launch_mfma_calibration(float* sink, int blocks, int iters, int data, hipStream_t stream);

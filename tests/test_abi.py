@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_header_declares_the_boundary():
     names = declared_functions()
-    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops", "attn_mfma_calibration", "attn_fwd_strided"}
+    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops", "attn_mfma_calibration", "attn_mfma_calibration_data", "attn_fwd_strided"}
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -97,6 +97,9 @@ def test_calibration_rejects_bad_arguments_without_a_gpu(lib):
     assert lib.attn_mfma_calibration(None, 256, 10, None) == -1.0
     assert lib.attn_mfma_calibration(A16, 0, 10, None) == -1.0
     assert lib.attn_mfma_calibration(A16, 256, 0, None) == -1.0
+    assert lib.attn_mfma_calibration_data(None, 256, 10, 2, None) == -1.0
+    assert lib.attn_mfma_calibration_data(A16, 256, 10, 4, None) == -1.0
+    assert lib.attn_mfma_calibration_data(A16, 256, 10, -1, None) == -1.0
 
 
 def test_python_binding_refuses_cpu_tensors():

@@ -19,6 +19,7 @@
 //     not MFMA phases, and the matrix pipe has work across it.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "gemm_layout.h"
 #include "gemm_launch.h"
@@ -79,6 +80,11 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
     constexpr int kStageA = T::kStageA, kStageB = T::kStageB, kBOffset = T::kBOffset;
     constexpr int kCopiers = T::kCopiers, kCopiesA = T::kCopiesA, kCopiesB = T::kCopiesB, RB = T::kNRowBytes;
     constexpr int kBK = T::BK, kKS = T::kKS, NS = T::NS, RBK = T::kRBK;
+    constexpr bool MI16 = T::MI == 16;
+    // blocks of the wavefront tile per MFMA shape: kRM x kRN result registers sets, kHalfM m-blocks per sub-step (MI16)
+    constexpr int kRM = MI16 ? T::kWaveM / 16 : kMB, kRN = MI16 ? gemm_layout::kWaveN / 16 : kNB, kHalfM = kRM / 2;
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    using Acc = std::conditional_t<MI16, f32x4, f32x16>;
     static_assert(kCopiesA == kCopiesB, "the copy schedule pairs one A with one B instruction");
     __shared__ __attribute__((aligned(16))) char smem[T::kLdsBytes + 256];   // stages, then the warm-up loads' sink
 
@@ -108,7 +114,7 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
             const int rb = min(n0 + kt_dma_row<RBK>(i, lane), N - 1) - n0;
             b_off[n] = (unsigned)rb * b_rb + 16u * (unsigned)kt_dma_chunk<RBK>(i, lane);
         } else {
-            const int col = min(n0 + 8 * nt_dma_chunk<RB>(i, lane), N - 8) - n0;    // columns past N re-read the last piece
+            const int col = min(n0 + 8 * nt_dma_chunk<RB, T::MI>(i, lane), N - 8) - n0;    // columns past N re-read the last piece
             b_off[n] = (unsigned)nt_dma_row<RB>(i, lane) * b_rb + 2u * (unsigned)col;
         }
     }
@@ -156,56 +162,97 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
     };
 
     // ---- per-lane LDS read addresses (stage 0; stage, block and sub-step offsets are immediates) ----
-    unsigned a_addr[kKS];            // second MFMA operand (lanes = m), block jm adds jm * 32 rows
-    unsigned b_addr[B_NK ? kKS : 2 * kNB];
+    // MI = 32: one address per 16-deep step; MI = 16: one per 32-deep step (entries 0 .. BK/32 - 1)
+    unsigned a_addr[kKS];            // second MFMA operand (lanes = m), block jm adds jm * 32 (16) rows
+    unsigned b_addr[B_NK ? kKS : 2 * kRN];
+    if constexpr (MI16) {
 #pragma unroll
-    for (int ks = 0; ks < kKS; ++ks) a_addr[ks] = lds_base + kt_offset<RBK>(kt_row(wm * kMB, lane), kt_chunk(ks, lane));
-    if constexpr (B_NK) {
+        for (int ks = 0; ks < kBK / 32; ++ks) a_addr[ks] = lds_base + kt_offset<RBK>(kt16_row(wm * kRM, lane), kt16_chunk(ks, lane));
+        if constexpr (B_NK) {
 #pragma unroll
-        for (int ks = 0; ks < kKS; ++ks) b_addr[ks] = lds_base + kBOffset + kt_offset<RBK>(kt_row(wn * kNB, lane), kt_chunk(ks, lane));
+            for (int ks = 0; ks < kBK / 32; ++ks) b_addr[ks] = lds_base + kBOffset + kt_offset<RBK>(kt16_row(wn * kRN, lane), kt16_chunk(ks, lane));
+        } else {
+#pragma unroll
+            for (int in = 0; in < kRN; ++in)
+#pragma unroll
+                for (int x = 0; x < 2; ++x) b_addr[2 * in + x] = lds_base + kBOffset + tr16_offset<RB>(wn * kRN + in, 0, x, lane);
+        }
     } else {
 #pragma unroll
-        for (int in = 0; in < kNB; ++in)
+        for (int ks = 0; ks < kKS; ++ks) a_addr[ks] = lds_base + kt_offset<RBK>(kt_row(wm * kMB, lane), kt_chunk(ks, lane));
+        if constexpr (B_NK) {
 #pragma unroll
-            for (int x = 0; x < 2; ++x) b_addr[2 * in + x] = lds_base + kBOffset + tr_offset<RB>(wn * kNB + in, 0, x, lane);
+            for (int ks = 0; ks < kKS; ++ks) b_addr[ks] = lds_base + kBOffset + kt_offset<RBK>(kt_row(wn * kNB, lane), kt_chunk(ks, lane));
+        } else {
+#pragma unroll
+            for (int in = 0; in < kNB; ++in)
+#pragma unroll
+                for (int x = 0; x < 2; ++x) b_addr[2 * in + x] = lds_base + kBOffset + tr_offset<RB>(wn * kNB + in, 0, x, lane);
+        }
     }
 
-    bf16x8 fa[2][kMB], fb[2][kNB];   // two operand sets: sub-step ks uses set ks & 1
+    // two operand sets.  MI = 32: sub-step ks (a 16-deep step) uses set ks & 1.  MI = 16: sub-step q covers the m-half
+    // q & 1 of the 32-deep step q >> 1: its A blocks are in set q & 1, the B blocks of the step in the set given by the
+    // parity of the step's number counted over the stage ring (consecutive steps alternate, also across stages).
+    bf16x8 fa[2][MI16 ? kHalfM : kMB], fb[2][kRN];
+    auto tr_pair = [&](unsigned addr_lo, unsigned addr_hi) __attribute__((always_inline)) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, (size_t)addr_lo));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, (size_t)addr_hi));
+        const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, v);
+    };
     auto read_frags = [&](auto bufc, auto ksc) __attribute__((always_inline)) {
         constexpr int buf = decltype(bufc)::value, ks = decltype(ksc)::value, set = ks & 1;
-        static_for<0, kMB>([&](auto jm) __attribute__((always_inline)) {
-            fa[set][jm.value] = *LDS_PTR(bf16x8, (size_t)(a_addr[ks] + buf * kStageA + jm.value * 32 * RBK));
-        });
-        static_for<0, kNB>([&](auto in) __attribute__((always_inline)) {
-            if constexpr (B_NK) {
-                fb[set][in.value] = *LDS_PTR(bf16x8, (size_t)(b_addr[ks] + buf * kStageB + in.value * 32 * RBK));
-            } else {
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    LDS_PTR(s16x4, (size_t)(b_addr[2 * in.value] + buf * kStageB + ks * 16 * RB)));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    LDS_PTR(s16x4, (size_t)(b_addr[2 * in.value + 1] + buf * kStageB + ks * 16 * RB)));
-                const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                fb[set][in.value] = __builtin_bit_cast(bf16x8, v);
-            }
-        });
+        if constexpr (MI16) {
+            constexpr int k32 = ks >> 1, mh = ks & 1, bset = (k32 + buf * (kBK / 32)) & 1;
+            static_for<0, kHalfM>([&](auto j) __attribute__((always_inline)) {
+                fa[set][j.value] = *LDS_PTR(bf16x8, (size_t)(a_addr[k32] + buf * kStageA + (mh * kHalfM + j.value) * 16 * RBK));
+            });
+            if constexpr (mh == 0)
+                static_for<0, kRN>([&](auto in) __attribute__((always_inline)) {
+                    if constexpr (B_NK) fb[bset][in.value] = *LDS_PTR(bf16x8, (size_t)(b_addr[k32] + buf * kStageB + in.value * 16 * RBK));
+                    else fb[bset][in.value] = tr_pair(b_addr[2 * in.value] + buf * kStageB + k32 * 32 * RB,
+                                                      b_addr[2 * in.value + 1] + buf * kStageB + k32 * 32 * RB);
+                });
+        } else {
+            static_for<0, kMB>([&](auto jm) __attribute__((always_inline)) {
+                fa[set][jm.value] = *LDS_PTR(bf16x8, (size_t)(a_addr[ks] + buf * kStageA + jm.value * 32 * RBK));
+            });
+            static_for<0, kNB>([&](auto in) __attribute__((always_inline)) {
+                if constexpr (B_NK) fb[set][in.value] = *LDS_PTR(bf16x8, (size_t)(b_addr[ks] + buf * kStageB + in.value * 32 * RBK));
+                else fb[set][in.value] = tr_pair(b_addr[2 * in.value] + buf * kStageB + ks * 16 * RB,
+                                                 b_addr[2 * in.value + 1] + buf * kStageB + ks * 16 * RB);
+            });
+        }
     };
 
-    f32x16 acc[kNB][kMB];
+    Acc acc[kRN][kRM];
 #pragma unroll
-    for (int in = 0; in < kNB; ++in)
+    for (int in = 0; in < kRN; ++in)
 #pragma unroll
-        for (int jm = 0; jm < kMB; ++jm)
+        for (int jm = 0; jm < kRM; ++jm)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[in][jm][r] = 0.0f;
+            for (int r = 0; r < (MI16 ? 4 : 16); ++r) acc[in][jm][r] = 0.0f;
 
-    auto mfma_set = [&](auto setc) __attribute__((always_inline)) {
-        constexpr int set = decltype(setc)::value;
-        static_for<0, kMB>([&](auto jm) __attribute__((always_inline)) {
-            static_for<0, kNB>([&](auto in) __attribute__((always_inline)) {
-                acc[in.value][jm.value] =
-                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][in.value], fa[set][jm.value], acc[in.value][jm.value], 0, 0, 0);
+    // the MFMAs of sub-step q
+    auto mfma_set = [&](auto bufc, auto qc) __attribute__((always_inline)) {
+        constexpr int q = decltype(qc)::value, set = q & 1;
+        if constexpr (MI16) {
+            constexpr int mh = q & 1, bset = ((q >> 1) + decltype(bufc)::value * (kBK / 32)) & 1;
+            static_for<0, kHalfM>([&](auto j) __attribute__((always_inline)) {
+                static_for<0, kRN>([&](auto in) __attribute__((always_inline)) {
+                    constexpr int jm = mh * kHalfM + j.value;
+                    acc[in.value][jm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[bset][in.value], fa[set][j.value], acc[in.value][jm], 0, 0, 0);
+                });
             });
-        });
+        } else {
+            static_for<0, kMB>([&](auto jm) __attribute__((always_inline)) {
+                static_for<0, kNB>([&](auto in) __attribute__((always_inline)) {
+                    acc[in.value][jm.value] =
+                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][in.value], fa[set][jm.value], acc[in.value][jm.value], 0, 0, 0);
+                });
+            });
+        }
     };
     auto wait_all = [&]() __attribute__((always_inline)) {
         __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) and lgkmcnt(0): own copies landed, own LDS reads returned
@@ -308,7 +355,7 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
                 if (copier && copy) static_for<kEarly, kCopiesA>([&](auto j) __attribute__((always_inline)) {
                     dma(U + NS - 1, IntC<DST>{}, j); dma(U + NS - 1, IntC<DST>{}, IntC<kCopiesA + j.value>{}); });
             }
-            mfma_set(IntC<ks.value & 1>{});
+            mfma_set(bufc, ks);
         });
         if (more) {
             wait_stage(U + 1, U + NS - 1);          // stage U+1 landed, own LDS reads returned
@@ -321,7 +368,7 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
             barrier();
             read_frags(IntC<NEXT>{}, IntC<0>{});
         }
-        mfma_set(IntC<(kKS - 1) & 1>{});
+        mfma_set(bufc, IntC<kKS - 1>{});
     };
     for (int U = 0;;) {
         bool done = false;
@@ -338,20 +385,34 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
     // ---- epilogue: C^T fragments -> bf16 -> this wavefront's 128 x 64 staging tile -> 16-byte stores ----
     // (no copy is in flight: the last stage was awaited before it was read)
     char* const stage = smem + wave * (kWaveM * 128);
-    const int half = lane >> 5;
+    if constexpr (MI16) {
 #pragma unroll
-    for (int in = 0; in < kNB; ++in)
+        for (int in = 0; in < kRN; ++in)
 #pragma unroll
-        for (int jm = 0; jm < kMB; ++jm)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int m = jm * 32 + (lane & 31);
-                const int n = in * 32 + 8 * g + 4 * half;
+            for (int jm = 0; jm < kRM; ++jm) {
+                const int m = jm * 16 + mfma16_rc(lane);
+                const int n = in * 16 + mfma16_out_row(lane, 0);
                 u32x2 v;
-                v[0] = pack_bf16x2(acc[in][jm][4 * g + 0], acc[in][jm][4 * g + 1]);
-                v[1] = pack_bf16x2(acc[in][jm][4 * g + 2], acc[in][jm][4 * g + 3]);
+                v[0] = pack_bf16x2(acc[in][jm][0], acc[in][jm][1]);
+                v[1] = pack_bf16x2(acc[in][jm][2], acc[in][jm][3]);
                 *(u32x2*)(stage + c_stage_offset(m, n)) = v;
             }
+    } else {
+        const int half = lane >> 5;
+#pragma unroll
+        for (int in = 0; in < kNB; ++in)
+#pragma unroll
+            for (int jm = 0; jm < kMB; ++jm)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int m = jm * 32 + (lane & 31);
+                    const int n = in * 32 + 8 * g + 4 * half;
+                    u32x2 v;
+                    v[0] = pack_bf16x2(acc[in][jm][4 * g + 0], acc[in][jm][4 * g + 1]);
+                    v[1] = pack_bf16x2(acc[in][jm][4 * g + 2], acc[in][jm][4 * g + 3]);
+                    *(u32x2*)(stage + c_stage_offset(m, n)) = v;
+                }
+    }
     __bf16* const ctile = p.c + (long long)(m0 + wm * kWaveM) * p.ldc + (n0 + wn * kWaveN);
 #pragma unroll
     for (int it = 0; it < kWaveM / 8; ++it) {
@@ -443,8 +504,8 @@ static void launch_tiled(GemmParams p, int b_is_nk, hipStream_t stream) {
 // four everywhere (a half-filled chip runs somewhat faster than the estimate, which never changed the order).
 int gemm_auto_tile(int M, int N) {
     struct Shape { int tile, edge, slots; double peak; };
-    static const Shape shapes[4] = {{256, 256, 256, 1330.0}, {128, 128, 512, 1150.0}, {1284, 128, 256, 880.0}, {64, 64, 512, 700.0}};
-    int best = 256;
+    static const Shape shapes[4] = {{25616, 256, 256, 1420.0}, {128, 128, 512, 1150.0}, {1284, 128, 256, 880.0}, {64, 64, 512, 700.0}};
+    int best = 25616;
     double best_rate = -1.0;
     for (const Shape& sh : shapes) {
         const long long tiles = (long long)((M + sh.edge - 1) / sh.edge) * ((N + sh.edge - 1) / sh.edge);
@@ -463,6 +524,11 @@ int gemm_launch(GemmParams p, int b_is_nk, bool tiled, int tile, hipStream_t str
         else if (tile == 256) launch_tiled<TileLarge>(p, b_is_nk, stream);
         else if (tile == 64) launch_tiled<TileTiny>(p, b_is_nk, stream);
         else if (tile == 1284) launch_tiled<TileSmall4>(p, b_is_nk, stream);
+        else if (tile == 25616) launch_tiled<TileLarge16>(p, b_is_nk, stream);
+        else if (tile == 256416) launch_tiled<TileLarge4_16>(p, b_is_nk, stream);
+        else if (tile == 12816) launch_tiled<TileSmall16>(p, b_is_nk, stream);
+        else if (tile == 128416) launch_tiled<TileSmall4_16>(p, b_is_nk, stream);
+        else if (tile == 6416) launch_tiled<TileTiny16>(p, b_is_nk, stream);
         else launch_tiled<TileSmall>(p, b_is_nk, stream);
     } else {
         p.tiles_m = (p.M + 63) / 64;

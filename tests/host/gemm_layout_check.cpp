@@ -13,6 +13,7 @@
 //      read-back map returns every (m, n) exactly once;
 //   5. workgroup id -> tile is a bijection for even and ragged tile grids;
 //   6. a planted swizzle mismatch between copy and operand read is detected by check 2.
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <set>
@@ -63,10 +64,10 @@ template <class T> static Img stage_nt() {
     int written = 0;
     for (int i = 0; i < kStageBytes / 1024; ++i)
         for (int lane = 0; lane < 64; ++lane) {
-            const int row = nt_dma_row<RB>(i, lane), chunk = nt_dma_chunk<RB>(i, lane);
+            const int row = nt_dma_row<RB>(i, lane), chunk = nt_dma_chunk<RB, T::MI>(i, lane);
             CHECK(row >= 0 && row < T::BK && chunk >= 0 && chunk < RB / 16, "bad source piece row %d chunk %d", row, chunk);
             const int dst = i * 1024 + lane * 16;
-            CHECK(dst == nt_offset<RB>(row, chunk), "copy destination %d != layout offset %d", dst, nt_offset<RB>(row, chunk));
+            CHECK(dst == (nt_offset<RB, T::MI>(row, chunk)), "copy destination %d != layout offset %d", dst, nt_offset<RB, T::MI>(row, chunk));
             for (int b = 0; b < 16; ++b) {
                 CHECK(t.row[dst + b] < 0, "LDS byte %d written twice", dst + b);
                 t.row[dst + b] = row; t.col[dst + b] = chunk * 8 + b / 2; ++written;
@@ -202,7 +203,89 @@ static void check_tile_coord() {
     }
 }
 
+// ---- the same checks for the 16x16x32 instruction (Tile::MI == 16) ----------------------------
+template <class T> static void check_mi16() {
+    constexpr int RBK = T::kRBK, RB = T::kNRowBytes, kK32 = T::BK / 32;
+    const Img kt = stage_kt<T>();
+    int mism = 0, planted = 0;
+    for (int blk = 0; blk < T::BM / 16; ++blk)
+        for (int ks = 0; ks < kK32; ++ks)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int row = kt16_row(blk, lane), chunk = kt16_chunk(ks, lane);
+                const int off = kt_offset<RBK>(row, chunk), off_bug = row * RBK + chunk * 16;
+                CHECK(off == kt_offset<RBK>(kt16_row(0, lane), kt16_chunk(ks, lane)) + blk * 16 * RBK, "block offset is not additive");
+                for (int e = 0; e < 8; ++e) {
+                    if (!(kt.row[off + 2 * e] == blk * 16 + mfma16_rc(lane) && kt.col[off + 2 * e] == ks * 32 + mfma16_k(lane, e))) ++mism;
+                    if (!(kt.row[off_bug + 2 * e] == blk * 16 + mfma16_rc(lane) && kt.col[off_bug + 2 * e] == ks * 32 + mfma16_k(lane, e))) ++planted;
+                }
+            }
+    CHECK(mism == 0, "16x16x32: k-major operand read does not conform (%d)", mism);
+    CHECK(planted > 0, "16x16x32: planted swizzle bug was not detected");
+    CHECK((T::NS - 1) * T::kStageA + (T::BM / T::WM / 16 - 1) * 16 * RBK < 65536, "immediate offset of a 16-byte read exceeds 16 bits");
+    const Img nt = stage_nt<T>();
+    for (int nb = 0; nb < T::BN / 16; ++nb)
+        for (int ks = 0; ks < kK32; ++ks)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int x = 0; x < 2; ++x) {
+                    CHECK(tr16_offset<RB>(nb, ks, x, lane) == tr16_offset<RB>(nb, 0, x, lane) + ks * 32 * RB, "32-deep step offset is not additive");
+                    for (int j = 0; j < 4; ++j) {
+                        const int src = tr_src_lane(lane, j);
+                        const int base = tr16_offset<RB>(nb, ks, x, src);
+                        const int off = base + 2 * tr_src_elem(lane);
+                        CHECK(off >= 0 && off + 2 <= T::kStageB && (base & 7) == 0, "bad transposing-read address %d", off);
+                        const int e = 4 * x + j;
+                        CHECK(nt.row[off] == ks * 32 + mfma16_k(lane, e), "16x16x32 k mismatch nb %d ks %d lane %d e %d: %d", nb, ks, lane, e, nt.row[off]);
+                        CHECK(nt.col[off] == nb * 16 + mfma16_rc(lane), "16x16x32 n mismatch nb %d lane %d e %d: %d", nb, lane, e, nt.col[off]);
+                    }
+                }
+    CHECK((T::NS - 1) * T::kStageB + (kK32 - 1) * 32 * RB < 65536, "immediate offset of a transposing read exceeds 16 bits");
+    // banks
+    for (int blk = 0; blk < T::BM / 16; ++blk)
+        for (int ks = 0; ks < kK32; ++ks)
+            for (int g = 0; g < 4; ++g) {
+                std::set<int> slots;
+                for (int l = 16 * g; l < 16 * g + 16; ++l) slots.insert((kt_offset<RBK>(kt16_row(blk, l), kt16_chunk(ks, l)) >> 4) & 15);
+                CHECK(slots.size() == 16, "16x16x32 16-byte read: bank conflict in lane group %d (blk %d ks %d)", g, blk, ks);
+            }
+    for (int nb = 0; nb < T::BN / 16; ++nb)
+        for (int ks = 0; ks < kK32; ++ks)
+            for (int x = 0; x < 2; ++x)
+                for (int h = 0; h < 2; ++h) {
+                    std::set<int> slots;
+                    for (int l = 32 * h; l < 32 * h + 32; ++l) slots.insert((tr16_offset<RB>(nb, ks, x, l) >> 3) & 31);
+                    CHECK(slots.size() == 32, "16x16x32 transposing read: bank conflict (nb %d ks %d x %d half %d)", nb, ks, x, h);
+                }
+    // C staging: 16 x 16 result blocks, a lane's 4 registers are 4 consecutive n of row m
+    constexpr int kWaveM = T::kWaveM;
+    std::vector<int> m_of(kWaveM * 128, -1), n_of(kWaveM * 128, -1);
+    for (int lane = 0; lane < 64; ++lane)
+        for (int in = 0; in < kWaveN / 16; ++in)
+            for (int jm = 0; jm < kWaveM / 16; ++jm)
+                for (int r = 0; r < 4; ++r) {
+                    const int m = jm * 16 + mfma16_rc(lane), n = in * 16 + mfma16_out_row(lane, r);
+                    const int off = c_stage_offset(m, n);
+                    CHECK(off >= 0 && off + 2 <= kWaveM * 128 && m_of[off] < 0, "16x16x32 C staging byte %d bad or written twice", off);
+                    m_of[off] = m; n_of[off] = n; m_of[off + 1] = m; n_of[off + 1] = n;
+                    if (r == 0) CHECK((off & 7) == 0 && c_stage_offset(m, n + 3) == off + 6, "quad not contiguous");
+                }
+    for (int it = 0; it < kWaveM / 8; ++it)
+        for (int lane = 0; lane < 64; ++lane) {
+            const int row = it * 8 + (lane >> 3), pos = lane & 7, col = 8 * (pos ^ cswz(row));
+            for (int e = 0; e < 8; ++e) {
+                const int off = row * 128 + pos * 16 + 2 * e;
+                CHECK(m_of[off] == row && n_of[off] == col + e, "16x16x32 read-back (%d,%d) finds (%d,%d)", row, col + e, m_of[off], n_of[off]);
+            }
+        }
+    for (int h = 0; h < 2; ++h) {                                  // write banks: 32 lanes x 8 bytes
+        std::vector<int> hits(32, 0);
+        int worst = 0;
+        for (int l = 32 * h; l < 32 * h + 32; ++l) worst = std::max(worst, ++hits[(c_stage_offset(mfma16_rc(l), mfma16_out_row(l, 0)) >> 3) & 31]);
+        CHECK(worst <= 1, "16x16x32 C staging write: %d lanes on one bank pair", worst);
+    }
+}
+
 template <class T> static void check_tile_shape() {
+    if constexpr (T::MI == 16) { check_mi16<T>(); return; }
     CHECK(check_kt_operand<T>(false) == 0, "k-major operand read does not conform");
     CHECK(check_kt_operand<T>(true) > 0, "planted swizzle bug was not detected");
     check_kt_addressing<T>();
@@ -217,6 +300,11 @@ int main() {
     check_tile_shape<TileSmall>();
     check_tile_shape<TileTiny>();
     check_tile_shape<TileSmall4>();
+    check_tile_shape<TileLarge16>();
+    check_tile_shape<TileLarge4_16>();
+    check_tile_shape<TileSmall16>();
+    check_tile_shape<TileSmall4_16>();
+    check_tile_shape<TileTiny16>();
     check_tile_coord();
     if (failures) { printf("%d gemm layout check(s) FAILED\n", failures); return 1; }
     printf("gemm layout checks passed\n");

@@ -126,10 +126,10 @@ def test_gemm_header_symbols_are_exported(lib):
     # the tile rule at the paper's square sizes and at the cross-overs it was measured on
     lib.gemm_bf16_auto_tile.restype = ctypes.c_int
     lib.gemm_bf16_auto_tile.argtypes = [ctypes.c_int, ctypes.c_int]
-    want = {1024: 64, 1280: 64, 1536: 1284, 2048: 1284, 2304: 128, 2560: 128, 3072: 256, 4096: 256, 8192: 256, 16384: 256}
+    want = {1024: 64, 1280: 64, 1536: 1284, 2048: 1284, 2304: 128, 2560: 128, 3072: 25616, 4096: 25616, 8192: 25616, 16384: 25616}
     assert {s: lib.gemm_bf16_auto_tile(s, s) for s in want} == want
-    rect = {(1024, 8192): 128, (8192, 1024): 128, (2048, 4096): 128, (1024, 4096): 1284, (1536, 8192): 256, (3000, 5000): 256,
-            (1024, 16384): 256, (256, 16384): 1284, (128, 4096): 64, (64, 1 << 20): 64}
+    rect = {(1024, 8192): 128, (8192, 1024): 128, (2048, 4096): 128, (1024, 4096): 1284, (1536, 8192): 25616, (3000, 5000): 25616,
+            (1024, 16384): 25616, (256, 16384): 1284, (128, 4096): 64, (64, 1 << 20): 64}
     assert {mn: lib.gemm_bf16_auto_tile(*mn) for mn in rect} == rect
     assert lib.gemm_bf16_auto_tile(0, 8) == 0
 
@@ -146,7 +146,7 @@ def test_gemm_argument_errors_are_reported_without_a_gpu(lib):
     assert g(lda=1 << 31) == -2
     assert g(M=(1 << 31) - 1, N=(1 << 31) - 1, ldb=(1 << 31) - 1, ldc=(1 << 31) - 1) == -2   # too many tiles
     assert g(a=A16 + 1) == -4 and g(c=A16 + 3) == -4  # odd addresses cannot hold bf16
-    assert lib.gemm_bf16_tile(A16, A16, A16, 256, 256, 64, 64, 256, 256, 0, 96, None) == -3   # tile must be 0, 64, 128, 1284, 256 or 2564
+    assert lib.gemm_bf16_tile(A16, A16, A16, 256, 256, 64, 64, 256, 256, 0, 96, None) == -3   # tile must be one of the shape codes of gemm.h
     assert lib.gemm_bf16_tile(None, A16, A16, 256, 256, 64, 64, 256, 256, 0, 128, None) == -1
 
 

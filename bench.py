@@ -102,7 +102,7 @@ def mfma_sustained_tflops(torch, lib, dev, stream, data=0):
     16x16x32 instruction (everything else, and every kernel of the library, uses 32x32x16)."""
     sink = torch.zeros(16, dtype=torch.float32, device=dev)
     blocks, sp = prop_cus(torch, dev), stream.cuda_stream
-    iters = 300000 if data == 0 else 150000
+    iters = 300000 if data == 0 else 150000     # kinds 4 and 5 run half the wavefronts: the same duration
     lib.attn_mfma_calibration_data(sink.data_ptr(), blocks, 2000, data, sp)
     torch.cuda.synchronize()
     c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -118,7 +118,9 @@ def mfma_sustained_by_operands(torch, lib, dev, stream):
     return {"zeros": mfma_sustained_tflops(torch, lib, dev, stream, 1),
             "smooth": mfma_sustained_tflops(torch, lib, dev, stream, 0),
             "normal": mfma_sustained_tflops(torch, lib, dev, stream, 2),
-            "normal_16x16x32": mfma_sustained_tflops(torch, lib, dev, stream, 3)}
+            "normal_16x16x32": mfma_sustained_tflops(torch, lib, dev, stream, 3),
+            "normal_16x16x32_one_wave_per_simd": mfma_sustained_tflops(torch, lib, dev, stream, 4),
+            "normal_one_wave_per_simd": mfma_sustained_tflops(torch, lib, dev, stream, 5)}
 
 
 INPUT_KINDS = {"normal": "synthetic",

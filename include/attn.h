@@ -112,7 +112,9 @@ double attn_mfma_calibration(float *sink, int blocks, int iters, void *stream);
  * lane, element and workgroup (the distribution of the benchmark inputs), 3 = the operands of 2 on the other
  * bf16 shape, v_mfma_f32_16x16x32_bf16 (every other kind and every kernel here use 32x32x16).  Kinds 1 and 2
  * issue 8*iters MFMAs per wavefront, kind 3 16*iters of the half-sized instruction: the same FLOPs, which the
- * return value counts.  Same error behaviour; any other `data` returns -1.0.
+ * return value counts.  Kinds 4 and 5 are kinds 3 and 2 with workgroups of 4 wavefronts, i.e. ONE wavefront per
+ * SIMD instead of two: what a schedule sustains in which only one wavefront of a SIMD issues MFMAs at a time.
+ * Same error behaviour; any other `data` returns -1.0.
  */
 double attn_mfma_calibration_data(float *sink, int blocks, int iters, int data, void *stream);
 

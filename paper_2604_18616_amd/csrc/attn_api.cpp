@@ -75,7 +75,7 @@ extern "C" double attn_mfma_calibration(float* sink, int blocks, int iters, void
 }
 
 extern "C" double attn_mfma_calibration_data(float* sink, int blocks, int iters, int data, void* stream) {
-    if (!sink || blocks <= 0 || iters <= 0 || data < 0 || data > 3) return -1.0;
+    if (!sink || blocks <= 0 || iters <= 0 || data < 0 || data > 5) return -1.0;
     return attn_launch_mfma_calibration(sink, blocks, iters, data, (hipStream_t)stream);
 }
 

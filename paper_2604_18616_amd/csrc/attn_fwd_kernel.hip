@@ -773,7 +773,8 @@ __global__ __launch_bounds__(512, 1) void mfma_calibration_kernel(float* sink, i
 // The same with operands of a chosen kind: the GPU runs against a power limit, and what the matrix pipe sustains
 // depends on how many operand bits toggle.  data 1: all zeros; data 2: values with the spread of a standard normal
 // (sums of four uniform hashes, scaled), different per lane, element and workgroup, eight operand pairs in rotation;
-// data 3: those on the 16x16x32 shape.
+// data 3: those on the 16x16x32 shape; data 4 and 5: the 16x16x32 and the 32x32x16 shape with ONE wavefront per SIMD
+// (workgroups of 4 wavefronts) instead of two.
 __device__ __forceinline__ float calibration_normal(unsigned x) {
     float s = 0.f;
 #pragma unroll
@@ -826,9 +827,11 @@ __global__ __launch_bounds__(512, 1) void mfma_calibration_data_kernel(float* si
 double attn_launch_mfma_calibration(float* sink, int blocks, int iters, int data, hipStream_t stream) {
     if (data == 0) hipLaunchKernelGGL(mfma_calibration_kernel, dim3((unsigned)blocks), dim3(512), 0, stream, sink, iters);
     else if (data == 3) hipLaunchKernelGGL(mfma_calibration_data_kernel<true>, dim3((unsigned)blocks), dim3(512), 0, stream, sink, iters, data);
+    else if (data == 4) hipLaunchKernelGGL(mfma_calibration_data_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, sink, iters, data);
+    else if (data == 5) hipLaunchKernelGGL(mfma_calibration_data_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, sink, iters, data);
     else hipLaunchKernelGGL(mfma_calibration_data_kernel<false>, dim3((unsigned)blocks), dim3(512), 0, stream, sink, iters, data);
     if (hipGetLastError() != hipSuccess) return -1.0;
-    return (double)blocks * 8.0 * (double)iters * (data == 0 ? 4.0 : 8.0) * 32768.0;   // 2*32*32*16 flop per MFMA
+    return (double)blocks * (data >= 4 ? 4.0 : 8.0) * (double)iters * (data == 0 ? 4.0 : 8.0) * 32768.0;   // wavefronts x MFMAs x 2*32*32*16 flop
 }
 
 // Host-side launcher: the only symbol the C-ABI translation unit needs from this file.

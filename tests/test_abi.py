@@ -98,7 +98,7 @@ def test_calibration_rejects_bad_arguments_without_a_gpu(lib):
     assert lib.attn_mfma_calibration(A16, 0, 10, None) == -1.0
     assert lib.attn_mfma_calibration(A16, 256, 0, None) == -1.0
     assert lib.attn_mfma_calibration_data(None, 256, 10, 2, None) == -1.0
-    assert lib.attn_mfma_calibration_data(A16, 256, 10, 4, None) == -1.0
+    assert lib.attn_mfma_calibration_data(A16, 256, 10, 6, None) == -1.0
     assert lib.attn_mfma_calibration_data(A16, 256, 10, -1, None) == -1.0
 
 

@@ -151,3 +151,20 @@ def test_full_size_configs_sampled_rows(name):
         assert np.array_equal(o[:, :, 0, :], np.repeat(vf[:, :, 0, :], g, axis=1))
     vmax = np.repeat(np.abs(vf).max(axis=2), g, axis=1)[:, :, None, :]
     assert (np.abs(o) <= vmax * (1 + 2 ** -7)).all()   # O is a convex combination of V rows
+
+
+def test_mfma_calibration_kernels_run_and_count_their_flops():
+    """The measurement aids of the bench: every operand kind launches, finishes and reports the FLOPs it issued
+    (8 or 4 wavefronts per workgroup x 4 or 8 MFMAs of 32768 flop per iteration, or as many FLOPs in 16x16x32)."""
+    import torch
+
+    from paper_2604_18616_amd import binding
+    lib = binding.load_library()
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda:0")
+    sp = torch.cuda.current_stream().cuda_stream
+    assert lib.attn_mfma_calibration(sink.data_ptr(), 64, 100, sp) == 64 * 8 * 100 * 4 * 32768.0
+    for data, waves, per_iter in ((0, 8, 4), (1, 8, 8), (2, 8, 8), (3, 8, 8), (4, 4, 8), (5, 4, 8)):
+        print("calibration kind", data, flush=True)
+        assert lib.attn_mfma_calibration_data(sink.data_ptr(), 64, 100, data, sp) == 64 * waves * 100 * per_iter * 32768.0
+    torch.cuda.synchronize()
+    assert float(sink.abs().sum()) == 0.0            # the sink is never written in practice

@@ -49,8 +49,10 @@ int gemm_bf16(const void *a, const void *b, void *c, int M, int N, int K,
  * 128 (128 x 128 tiles in two stages, two workgroups per CU), 1284 (128 x 128 tiles in four stages,
  * one per CU), 64 (64 x 64 tiles by two wavefronts, four stages): these run v_mfma_f32_32x32x16_bf16.
  * The same five shapes on v_mfma_f32_16x16x32_bf16, which takes less power per FLOP and is faster wherever the
- * power limit sets the clock (large products of normally distributed data): 25616, 256416, 12816, 128416, 6416.
- * 0 = what gemm_bf16 does: of 25616, 128, 1284 and 64 the shape with the best estimate of (throughput of the
+ * power limit sets the clock (large products of normally distributed data): 25616, 256416, 12816, 128416, 6416;
+ * and 19216: 192 x 256 tiles (192 rows of C) on that instruction, for results that 256 x 256 tiles cut into a
+ * poor number of workgroups (3072 x 3072: 192 instead of 144 for 256 CUs).
+ * 0 = what gemm_bf16 does: of 25616, 19216, 128, 1284 and 64 the shape with the best estimate of (throughput of the
  * shape on a full chip) x (how full its last round of workgroups leaves the 256 CUs); see gemm_bf16_auto_tile.
  * Any other value: ATTN_ERR_UNSUPPORTED.  Shapes that only the general kernel can take ignore the choice.
  * For tuning and for tests.
@@ -59,7 +61,7 @@ int gemm_bf16_tile(const void *a, const void *b, void *c, int M, int N, int K,
                    long long lda, long long ldb, long long ldc, int b_is_nk, int tile, void *stream);
 
 /* The tile gemm_bf16 takes for an M x N result when its operands qualify for the matrix-core kernel: 64, 128,
- * 1284 or 25616 as described above (0 for invalid sizes).  Host-only helper, for tuning and for tests. */
+ * 1284, 19216 or 25616 as described above (0 for invalid sizes).  Host-only helper, for tuning and for tests. */
 int gemm_bf16_auto_tile(int M, int N);
 
 /* Algorithmic FLOPs of one gemm_bf16 call: 2*M*N*K (0 for invalid sizes).  Host-only helper. */

@@ -136,7 +136,7 @@ def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
 def gemm_bf16(a, b, c=None, b_is_nk=False, stream=None, tile=0):
     """C = A B for bf16 CUDA tensors a [M,K] and b [K,N] (or [N,K] if b_is_nk); rows contiguous,
     row pitch free.  c (bf16 [M,N]) is allocated with torch if not given.  Enqueued on `stream`
-    (default: torch's current stream); no sync.  tile: 0 (by size) or a shape code of gemm.h: 64, 128, 1284, 256, 2564, or those with 16 appended (gemm_bf16_tile)."""
+    (default: torch's current stream); no sync.  tile: 0 (by size) or a shape code of gemm.h: 64, 128, 1284, 256, 2564, those with 16 appended, or 19216 (gemm_bf16_tile)."""
     import torch
 
     if not (a.is_cuda and b.is_cuda):

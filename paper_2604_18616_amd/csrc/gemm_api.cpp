@@ -9,7 +9,7 @@
 extern "C" int gemm_bf16_tile(const void* a, const void* b, void* c, int M, int N, int K,
                               long long lda, long long ldb, long long ldc, int b_is_nk, int tile, void* stream) {
     if (!a || !b || !c) return ATTN_ERR_NULL_PTR;
-    if (tile != 0 && tile != 64 && tile != 128 && tile != 256 && tile != 2564 && tile != 1284 && tile != 25616 && tile != 256416 && tile != 12816 && tile != 128416 && tile != 6416) return ATTN_ERR_UNSUPPORTED;
+    if (tile != 0 && tile != 64 && tile != 128 && tile != 256 && tile != 2564 && tile != 1284 && tile != 25616 && tile != 19216 && tile != 256416 && tile != 12816 && tile != 128416 && tile != 6416) return ATTN_ERR_UNSUPPORTED;
     if (M <= 0 || N <= 0 || K <= 0) return ATTN_ERR_BAD_SHAPE;
     if (lda < K || ldb < (b_is_nk ? K : N) || ldc < N) return ATTN_ERR_BAD_SHAPE;
     if (lda >= (1LL << 31) || ldb >= (1LL << 31) || ldc >= (1LL << 31)) return ATTN_ERR_BAD_SHAPE;

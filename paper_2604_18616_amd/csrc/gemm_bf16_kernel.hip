@@ -85,7 +85,7 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
     constexpr int kRM = MI16 ? T::kWaveM / 16 : kMB, kRN = MI16 ? gemm_layout::kWaveN / 16 : kNB, kHalfM = kRM / 2;
     typedef __attribute__((ext_vector_type(4))) float f32x4;
     using Acc = std::conditional_t<MI16, f32x4, f32x16>;
-    static_assert(kCopiesA == kCopiesB, "the copy schedule pairs one A with one B instruction");
+    static_assert(kCopiesA <= kCopiesB, "the copy schedule pairs A with B instructions and ends with the B instructions left over");
     __shared__ __attribute__((aligned(16))) char smem[T::kLdsBytes + 256];   // stages, then the warm-up loads' sink
 
     const int tid = threadIdx.x;
@@ -110,6 +110,10 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
         const int i = w4 + kCopiers * n;
         const int ra = min(m0 + kt_dma_row<RBK>(i, lane), M - 1) - m0;               // rows past M re-read row M-1
         a_off[n] = (unsigned)ra * a_rb + 16u * (unsigned)kt_dma_chunk<RBK>(i, lane);
+    }
+#pragma unroll
+    for (int n = 0; n < kCopiesB; ++n) {
+        const int i = w4 + kCopiers * n;
         if constexpr (B_NK) {
             const int rb = min(n0 + kt_dma_row<RBK>(i, lane), N - 1) - n0;
             b_off[n] = (unsigned)rb * b_rb + 16u * (unsigned)kt_dma_chunk<RBK>(i, lane);
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
     auto dma = [&](int U, auto bufc, auto jc) __attribute__((always_inline)) {
         constexpr int buf = decltype(bufc)::value;
         constexpr int j = decltype(jc)::value;
-        constexpr int n = j % kCopiesA;
+        constexpr int n = j < kCopiesA ? j : j - kCopiesA;
         const int i = w4 + kCopiers * n;
         if constexpr (j < kCopiesA) {
             unsigned off = a_off[n];
@@ -154,6 +158,11 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
                     const int i = w4 + kCopiers * n;
                     const unsigned dst = i * 1024 + lane * 16;
                     if (U * kBK + 8 * kt_dma_chunk<RBK>(i, lane) >= K) *(u32x4*)(smem + buf * kStageA + dst) = u32x4{0u, 0u, 0u, 0u};
+                }
+#pragma unroll
+                for (int n = 0; n < kCopiesB; ++n) {
+                    const int i = w4 + kCopiers * n;
+                    const unsigned dst = i * 1024 + lane * 16;
                     const bool b_past = B_NK ? (U * kBK + 8 * kt_dma_chunk<RBK>(i, lane) >= K) : (U * kBK + nt_dma_row<RB>(i, lane) >= K);
                     if (b_past) *(u32x4*)(smem + kBOffset + buf * kStageB + dst) = u32x4{0u, 0u, 0u, 0u};
                 }
@@ -282,17 +291,19 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
 #define GEMM_EARLY 2
 #endif
     constexpr int kEarly = GEMM_EARLY < kCopiesA ? GEMM_EARLY : kCopiesA;                 // copy pairs (A, B) issued in the first sub-step, the rest in the second
+    // issue order of a stage's copies: A part, B part in turn, then the B parts left over (kCopiesA <= kCopiesB)
+    constexpr auto nth_copy = [](int n) constexpr { return n < 2 * kCopiesA ? ((n & 1) ? kCopiesA + n / 2 : n / 2) : n; };
     constexpr int kAhead = GEMM_AHEAD;                 // 0 switches the warm-up off
     const int nK_whole = KTAIL ? nK - 1 : nK;          // stages that lie wholly inside K
     const bool warmer = kAhead > 0 && T::kWaves == 8 && NS == 2 && (wave == 4 || wave == 5);
     unsigned warm_off;
     constexpr int kShareA = 32 / GEMM_GM, kShareB = GEMM_GM;      // workgroups of an XCD's patch that read the same A / B panel
-    static_assert(256 / kShareA <= 64 && 256 / kShareB <= 64, "one warm-up instruction per wavefront");
+    static_assert(kBM / kShareA <= 64 && kBN / kShareB <= 64, "one warm-up instruction per wavefront");
     if (wave == 4) {
-        const int r = (tc.tn % kShareA) * (256 / kShareA) + lane % (256 / kShareA);
+        const int r = (tc.tn % kShareA) * (kBM / kShareA) + lane % (kBM / kShareA);
         warm_off = (unsigned)(min(m0 + r, M - 1) - m0) * a_rb;
     } else {
-        const int r = (tc.tm % kShareB) * (256 / kShareB) + lane % (256 / kShareB);
+        const int r = (tc.tm % kShareB) * (kBN / kShareB) + lane % (kBN / kShareB);
         if (B_NK) warm_off = (unsigned)(min(n0 + r, N - 1) - n0) * b_rb;
         else warm_off = (unsigned)(r >> 2) * b_rb + 2u * (unsigned)(min(n0 + 64 * (r & 3), N - 2) - n0);
     }
@@ -343,17 +354,17 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
         static_for<0, kKS - 1>([&](auto ks) __attribute__((always_inline)) {
             read_frags(bufc, IntC<ks.value + 1>{});
             if constexpr (ks.value == 0) {
-                constexpr int first = kKS > 2 ? kEarly : kCopiesA;   // with two sub-steps everything goes here
+                constexpr int first = kKS > 2 ? 2 * kEarly : kPerStage;   // with two sub-steps everything goes here
                 if (copier) {
-                    if (copy) static_for<0, first>([&](auto j) __attribute__((always_inline)) {
-                        dma(U + NS - 1, IntC<DST>{}, j); dma(U + NS - 1, IntC<DST>{}, IntC<kCopiesA + j.value>{}); });
+                    if (copy) static_for<0, first>([&](auto n) __attribute__((always_inline)) {
+                        dma(U + NS - 1, IntC<DST>{}, IntC<nth_copy(n.value)>{}); });
                 } else if (warmer && U + kAhead < nK_whole) {
                     warm(U + kAhead);
                 }
             }
             if constexpr (ks.value == 1) {
-                if (copier && copy) static_for<kEarly, kCopiesA>([&](auto j) __attribute__((always_inline)) {
-                    dma(U + NS - 1, IntC<DST>{}, j); dma(U + NS - 1, IntC<DST>{}, IntC<kCopiesA + j.value>{}); });
+                if (copier && copy) static_for<2 * kEarly, kPerStage>([&](auto n) __attribute__((always_inline)) {
+                    dma(U + NS - 1, IntC<DST>{}, IntC<nth_copy(n.value)>{}); });
             }
             mfma_set(bufc, ks);
         });
@@ -496,21 +507,22 @@ static void launch_tiled(GemmParams p, int b_is_nk, hipStream_t stream) {
 
 // Tile-size choice: the shape that promises the most throughput, estimated as (what the shape delivers when
 // every CU has its fill of workgroups) x (how full the last round of workgroups leaves the chip) x (the share of
-// the tiles' area that lies inside the result).  The first
-// factor is measured on large squares (TFLOP/s: 256 x 256 tiles 1330, 128 x 128 in two stages with two
+// the tiles' area that lies inside the result).  The first factor is measured on large squares (TFLOP/s: 256 x 256
+// tiles on the 16x16x32 instruction 1420, 192 x 256 tiles on it 1300, 128 x 128 in two stages with two
 // workgroups per CU 1150, in four stages with one per CU 880, 64 x 64 with two per CU 700); the second is
 // tiles / (slots x rounds) with 256 CUs x workgroups per CU slots.  Checked against measurements on squares from
-// 1024 to 4096 and on rectangles from 1024 x 4096 to 1024 x 16384 and 3000 x 5000: it picks the fastest of the
-// four everywhere (a half-filled chip runs somewhat faster than the estimate, which never changed the order).
+// 1024 to 6144 and on rectangles from 1024 x 4096 to 1024 x 16384 and 3000 x 5000: it picks the fastest of the
+// five everywhere (a half-filled chip runs somewhat faster than the estimate, which never changed the order).
 int gemm_auto_tile(int M, int N) {
-    struct Shape { int tile, edge, slots; double peak; };
-    static const Shape shapes[4] = {{25616, 256, 256, 1420.0}, {128, 128, 512, 1150.0}, {1284, 128, 256, 880.0}, {64, 64, 512, 700.0}};
+    struct Shape { int tile, edge_m, edge_n, slots; double peak; };
+    static const Shape shapes[5] = {{25616, 256, 256, 256, 1420.0}, {19216, 192, 256, 256, 1300.0}, {128, 128, 128, 512, 1150.0},
+                                    {1284, 128, 128, 256, 880.0}, {64, 64, 64, 512, 700.0}};
     int best = 25616;
     double best_rate = -1.0;
     for (const Shape& sh : shapes) {
-        const long long tiles = (long long)((M + sh.edge - 1) / sh.edge) * ((N + sh.edge - 1) / sh.edge);
+        const long long tiles = (long long)((M + sh.edge_m - 1) / sh.edge_m) * ((N + sh.edge_n - 1) / sh.edge_n);
         const long long rounds = (tiles + sh.slots - 1) / sh.slots;
-        const double useful = (double)M * (double)N / ((double)tiles * sh.edge * sh.edge);   // edge tiles compute padding
+        const double useful = (double)M * (double)N / ((double)tiles * sh.edge_m * sh.edge_n);   // edge tiles compute padding
         const double rate = sh.peak * useful * (double)tiles / (double)(rounds * sh.slots);
         if (rate > best_rate) { best_rate = rate; best = sh.tile; }
     }
@@ -525,6 +537,7 @@ int gemm_launch(GemmParams p, int b_is_nk, bool tiled, int tile, hipStream_t str
         else if (tile == 64) launch_tiled<TileTiny>(p, b_is_nk, stream);
         else if (tile == 1284) launch_tiled<TileSmall4>(p, b_is_nk, stream);
         else if (tile == 25616) launch_tiled<TileLarge16>(p, b_is_nk, stream);
+        else if (tile == 19216) launch_tiled<TileTall16>(p, b_is_nk, stream);
         else if (tile == 256416) launch_tiled<TileLarge4_16>(p, b_is_nk, stream);
         else if (tile == 12816) launch_tiled<TileSmall16>(p, b_is_nk, stream);
         else if (tile == 128416) launch_tiled<TileSmall4_16>(p, b_is_nk, stream);

@@ -28,7 +28,9 @@ constexpr int kWaveN = 64;                      // every wavefront tile is 64 wi
 //                                for the smallest problems, where the time is the L2 -> LDS traffic of the
 //                                busiest CU and spreading it over every CU matters more than operand reuse.
 //   Tile<256, 256, 2, 4, 64, 2, 16>: the large-problem shape on v_mfma_f32_16x16x32_bf16 (MI = 16), the instruction
-//                                that takes less power per FLOP on normally distributed operands.
+//                                that takes less power per FLOP on normally distributed operands;
+//   Tile<192, 256, 2, 4, 64, 2, 16>: 192 rows of C (wavefront tile 96 x 64, 24 KB of A and 32 KB of B per stage) for
+//                                results that 256 x 256 tiles cut into a poor number of workgroups.
 template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int MI_ = 32>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_, MI = MI_;
@@ -56,6 +58,7 @@ using TileTiny = Tile<64, 64, 2, 1, 64, 4>;
 using TileSmall4 = Tile<128, 128, 2, 2, 64, 4>;
 using TileLarge16 = Tile<256, 256, 2, 4, 64, 2, 16>;
 using TileLarge4_16 = Tile<256, 256, 2, 4, 32, 4, 16>;
+using TileTall16 = Tile<192, 256, 2, 4, 64, 2, 16>;      // 192 x 256: for results that 256 x 256 tiles cut into a poor number of workgroups
 using TileSmall16 = Tile<128, 128, 2, 2, 64, 2, 16>;
 using TileSmall4_16 = Tile<128, 128, 2, 2, 64, 4, 16>;
 using TileTiny16 = Tile<64, 64, 2, 1, 64, 4, 16>;

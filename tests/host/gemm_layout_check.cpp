@@ -301,6 +301,7 @@ int main() {
     check_tile_shape<TileTiny>();
     check_tile_shape<TileSmall4>();
     check_tile_shape<TileLarge16>();
+    check_tile_shape<TileTall16>();
     check_tile_shape<TileLarge4_16>();
     check_tile_shape<TileSmall16>();
     check_tile_shape<TileSmall4_16>();

@@ -126,9 +126,10 @@ def test_gemm_header_symbols_are_exported(lib):
     # the tile rule at the paper's square sizes and at the cross-overs it was measured on
     lib.gemm_bf16_auto_tile.restype = ctypes.c_int
     lib.gemm_bf16_auto_tile.argtypes = [ctypes.c_int, ctypes.c_int]
-    want = {1024: 64, 1280: 64, 1536: 1284, 2048: 1284, 2304: 128, 2560: 128, 3072: 25616, 4096: 25616, 8192: 25616, 16384: 25616}
+    want = {1024: 64, 1280: 64, 1536: 1284, 2048: 1284, 2304: 128, 2560: 128, 2816: 128, 3072: 19216, 3328: 19216, 3584: 25616, 3840: 25616,
+            4096: 25616, 4608: 19216, 5120: 25616, 6144: 19216, 7168: 25616, 8192: 25616, 16384: 25616}
     assert {s: lib.gemm_bf16_auto_tile(s, s) for s in want} == want
-    rect = {(1024, 8192): 128, (8192, 1024): 128, (2048, 4096): 128, (1024, 4096): 1284, (1536, 8192): 25616, (3000, 5000): 25616,
+    rect = {(1024, 8192): 128, (8192, 1024): 128, (2048, 4096): 128, (1024, 4096): 1284, (1536, 8192): 19216, (3072, 8192): 19216, (6144, 4096): 19216, (3000, 5000): 25616,
             (1024, 16384): 25616, (256, 16384): 1284, (128, 4096): 64, (64, 1 << 20): 64}
     assert {mn: lib.gemm_bf16_auto_tile(*mn) for mn in rect} == rect
     assert lib.gemm_bf16_auto_tile(0, 8) == 0

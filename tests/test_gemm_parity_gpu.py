@@ -74,14 +74,14 @@ TILED = [(256, 256, 32), (256, 256, 64), (256, 256, 96), (256, 256, 128), (256, 
          (1, 8, 8), (257, 8, 24), (8, 520, 136), (513, 512, 64)]
 
 
-@pytest.mark.parametrize("tile", [64, 128, 1284, 256, 2564, 25616, 256416, 12816, 128416, 6416])
+@pytest.mark.parametrize("tile", [64, 128, 1284, 256, 2564, 25616, 256416, 12816, 128416, 6416, 19216])
 @pytest.mark.parametrize("b_is_nk", [False, True])
 @pytest.mark.parametrize("M,N,K", TILED)
 def test_tiled_kernel_small_shapes(M, N, K, b_is_nk, tile):
     check_full(M, N, K, b_is_nk, seed=100 + M + N + K, tile=tile)
 
 
-@pytest.mark.parametrize("tile", [64, 128, 1284, 256, 2564, 25616, 256416, 12816, 128416, 6416])
+@pytest.mark.parametrize("tile", [64, 128, 1284, 256, 2564, 25616, 256416, 12816, 128416, 6416, 19216])
 @pytest.mark.parametrize("b_is_nk", [False, True])
 def test_tiled_kernel_padded_pitches(b_is_nk, tile):
     check_full(264, 272, 200, b_is_nk, seed=7, pad=(8, 16, 24), tile=tile)
@@ -102,7 +102,7 @@ def test_exact_small_integers():
     B = rng.integers(-3, 4, size=(128, 256)).astype(np.float32)
     want = A.astype(np.float64) @ B.astype(np.float64)
     assert np.abs(want).max() <= 256                   # integers up to 256 are exact in bf16
-    for tile in (64, 128, 1284, 256, 2564, 25616, 256416, 12816, 128416, 6416):
+    for tile in (64, 128, 1284, 256, 2564, 25616, 256416, 12816, 128416, 6416, 19216):
         assert np.array_equal(run(I.f32_to_bf16_bits(A), I.f32_to_bf16_bits(B), False, tile=tile), want)
 
 

@@ -1,11 +1,14 @@
-// bf16 GEMM for gfx950 (MI355X): C = A B with fp32 accumulation on v_mfma_f32_32x32x16_bf16
-// (the GEMM workload of the paper's Section 8; Table 2 names the ingredients: software
+// bf16 GEMM for gfx950 (MI355X): C = A B with fp32 accumulation on v_mfma_f32_16x16x32_bf16 or
+// v_mfma_f32_32x32x16_bf16 (the GEMM workload of the paper's Section 8; Table 2 names the ingredients: software
 // pipelining, MFMA, asynchronous copies, bank-conflict-free LDS layouts, vectorised access,
 // workgroup swizzling, guarded edge handling, explicit scheduling).
 //
-// Tiled kernel: one workgroup of 8 wavefronts owns a 256 x 256 tile of C, wavefront (wm, wn) a
-// 128 (m) x 64 (n) part of it as 4 x 2 MFMA tiles of the TRANSPOSED product (rows = n, lanes =
-// m), so that a lane ends up holding 4 consecutive n of one C row.  A and B stream through LDS
+// Tiled kernel, described for its largest shape (the template parameter Tile gives the others: 192 x 256, 128 x 128
+// and 64 x 64 tiles, two or four LDS stages, either MFMA instruction): one workgroup of 8 wavefronts owns a 256 x 256
+// tile of C, wavefront (wm, wn) a 128 (m) x 64 (n) part of it as MFMA tiles of the TRANSPOSED product (rows = n,
+// lanes = m), so that a lane ends up holding 4 consecutive n of one C row.  The 16x16x32 instruction does the same
+// FLOPs in twice the instructions and takes less power per FLOP, which is what limits large products on this GPU;
+// its sub-steps are the two m-halves of a 32-deep reduction step instead of 16-deep steps over the whole tile.  A and B stream through LDS
 // in 64-deep k stages, copied HBM -> LDS by global_load_lds_dwordx4 (no staging registers) into
 // XOR-swizzled tiles that the operand reads hit without bank conflicts.  B stored [K,N] is read
 // through ds_read_b64_tr_b16, which delivers the k-major MFMA operand from the n-major tile.

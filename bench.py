@@ -337,6 +337,9 @@ def main() -> int:
     if args.workload in I.GEMM_WORKLOADS:
         return bench_gemm(args, torch, lib, binding, I, dev)
     if args.workload in I.MOE_WORKLOADS:
+        if args.inputs != "normal":
+            print("bench.py: --inputs applies to the attention and GEMM workloads only", file=sys.stderr)
+            return 2
         return bench_moe(args, torch, lib, binding, I, dev)
     w = I.WORKLOADS[args.workload]
     qb, kb, vb = I.make_qkv(w)

@@ -168,3 +168,24 @@ def test_mfma_calibration_kernels_run_and_count_their_flops():
         assert lib.attn_mfma_calibration_data(sink.data_ptr(), 64, 100, data, sp) == 64 * waves * 100 * per_iter * 32768.0
     torch.cuda.synchronize()
     assert float(sink.abs().sum()) == 0.0            # the sink is never written in practice
+
+
+@pytest.mark.parametrize("kind", ["zeros", "constants"])
+@pytest.mark.parametrize("causal", [False, True])
+def test_uniform_scores(kind, causal):
+    """Degenerate inputs: every score of a row is equal (all-zero tensors, or one constant per tensor), so the softmax
+    is uniform over the visible keys, O is the mean of V (the constant) and LSE = score + log(number of visible keys).
+    Checked against the reference and against that closed form; ragged sizes through the 256-row kernel."""
+    w = small("uniform_" + kind, 1, 4, 2, 300, 333, 128, causal, 41)
+    q, k, v = I.make_qkv(w)
+    cq, ck, cv = (0.0, 0.0, 0.0) if kind == "zeros" else (0.5, 0.25, 1.5)
+    for arr, c in ((q, cq), (k, ck), (v, cv)):
+        arr[...] = I.f32_to_bf16_bits(np.full(1, c, dtype=np.float32))[0]
+    o, lse = run_hip(q, k, v, w.causal, w.scale)
+    o_ref, lse_ref = oracle_parallel(q, k, v, w.causal, w.scale)
+    print(w.name, check(o, lse, o_ref, lse_ref, w.name))
+    visible = np.clip(np.arange(w.Sq) + (w.Sk - w.Sq) + 1, 0, w.Sk) if causal else np.full(w.Sq, w.Sk)
+    assert visible.min() >= 1
+    assert np.abs(o - cv).max() <= 2.0 ** -8 * abs(cv)                       # the mean of a constant, rounded once to bf16
+    want = cq * ck * w.D * w.scale + np.log(visible)
+    assert np.abs(lse - want[None, None, :]).max() <= 1e-3

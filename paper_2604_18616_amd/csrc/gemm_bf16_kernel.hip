@@ -294,8 +294,6 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
 #define GEMM_EARLY 2
 #endif
     constexpr int kEarly = GEMM_EARLY < kCopiesA ? GEMM_EARLY : kCopiesA;                 // copy pairs (A, B) issued in the first sub-step, the rest in the second
-    // issue order of a stage's copies: A part, B part in turn, then the B parts left over (kCopiesA <= kCopiesB)
-    constexpr auto nth_copy = [](int n) constexpr { return n < 2 * kCopiesA ? ((n & 1) ? kCopiesA + n / 2 : n / 2) : n; };
     constexpr int kAhead = GEMM_AHEAD;                 // 0 switches the warm-up off
     const int nK_whole = KTAIL ? nK - 1 : nK;          // stages that lie wholly inside K
     const bool warmer = kAhead > 0 && T::kWaves == 8 && NS == 2 && (wave == 4 || wave == 5);
@@ -360,14 +358,14 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
                 constexpr int first = kKS > 2 ? 2 * kEarly : kPerStage;   // with two sub-steps everything goes here
                 if (copier) {
                     if (copy) static_for<0, first>([&](auto n) __attribute__((always_inline)) {
-                        dma(U + NS - 1, IntC<DST>{}, IntC<nth_copy(n.value)>{}); });
+                        dma(U + NS - 1, IntC<DST>{}, IntC<copy_order(n.value, kCopiesA)>{}); });
                 } else if (warmer && U + kAhead < nK_whole) {
                     warm(U + kAhead);
                 }
             }
             if constexpr (ks.value == 1) {
                 if (copier && copy) static_for<2 * kEarly, kPerStage>([&](auto n) __attribute__((always_inline)) {
-                    dma(U + NS - 1, IntC<DST>{}, IntC<nth_copy(n.value)>{}); });
+                    dma(U + NS - 1, IntC<DST>{}, IntC<copy_order(n.value, kCopiesA)>{}); });
             }
             mfma_set(bufc, ks);
         });

@@ -118,6 +118,11 @@ GEMM_HD int tr_src_elem(int lane) { return lane & 3; }
 template <int RB> GEMM_HD int nt_dma_row(int i, int lane) { return (1024 / RB) * i + lane / (RB / 16); }
 template <int RB, int MI = 32> GEMM_HD int nt_dma_chunk(int i, int lane) { return (lane % (RB / 16)) ^ nswz<RB, MI>(nt_dma_row<RB>(i, lane)); }
 
+// ---- issue order of a stage's copy instructions ---------------------------------------------------
+// Per copying wavefront a stage has ca parts of A (numbered 0 .. ca-1) and cb >= ca parts of B (numbered ca .. ca+cb-1).
+// They are issued A part, B part in turn, then the B parts left over: position n of the order is part
+GEMM_HD int copy_order(int n, int ca) { return n < 2 * ca ? ((n & 1) ? ca + n / 2 : n / 2) : n; }
+
 // ---- C staging (epilogue): per wavefront kWaveM rows (m) x 128 bytes (64 n) ------------------
 GEMM_HD int cswz(int m) { return (m >> 1) & 7; }
 GEMM_HD int c_stage_offset(int m, int n) { return m * 128 + (((n >> 3) ^ cswz(m)) << 4) + ((n & 7) << 1); }

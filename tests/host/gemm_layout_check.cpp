@@ -52,6 +52,15 @@ template <class T> static Img stage_kt() {
     std::set<int> seen;
     for (int w = 0; w < T::kCopiers; ++w) for (int n = 0; n < T::kCopiesA; ++n) seen.insert(w + T::kCopiers * n);
     CHECK((int)seen.size() == kStageBytes / 1024 && *seen.rbegin() == kStageBytes / 1024 - 1, "copy instructions not covered once");
+    // the issue order of a stage's copies visits every part of A and of B exactly once
+    CHECK(T::kCopiesA <= T::kCopiesB, "the copy order assumes at least as many B parts as A parts");
+    std::set<int> parts;
+    for (int n = 0; n < T::kCopiesA + T::kCopiesB; ++n) {
+        const int j = copy_order(n, T::kCopiesA);
+        CHECK(j >= 0 && j < T::kCopiesA + T::kCopiesB, "copy order position %d names part %d", n, j);
+        parts.insert(j);
+    }
+    CHECK((int)parts.size() == T::kCopiesA + T::kCopiesB, "copy order covers %zu of %d parts", parts.size(), T::kCopiesA + T::kCopiesB);
     CHECK(T::kPerCU * (T::kLdsBytes + 256) <= 160 * 1024, "LDS budget");
     CHECK(T::kWaves * T::kWaveM * 128 <= T::kLdsBytes, "C staging does not fit the stage buffers");
     return t;

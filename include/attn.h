@@ -1,7 +1,7 @@
 /*
  * attn.h -- C ABI of the MI355X (gfx950) flash-attention forward library.
  *
- * Operation (paper Section 2, "standard attention": S = Q K^T, P = softmax(S)
+ * Operation (the attention definition of the paper's "Motivating Example": S = Q K^T, P = softmax(S)
  * row-wise, O = P V, computed tile by tile with an online softmax so that S is
  * never materialised; Figure 1 gives the tiled kernel this library re-designs
  * for CDNA4):
@@ -12,7 +12,7 @@
  *     O[b,h,i,:] = sum_{j in J(i)} exp(s_ij - lse_i) * V[b,hk,j,:]
  *
  * The paper's definition carries no scale; the workload it evaluates is causal
- * grouped-query attention in bf16 with fp32 accumulation (Section 8, Figure 1:
+ * grouped-query attention in bf16 with fp32 accumulation (Evaluation, "Kernel Performance"; Figure 1:
  * kv head = q head / gqa).  Scores, running max / sum and the output
  * accumulator are fp32; only P is rounded to bf16 (as the second MFMA operand)
  * and O is rounded once, to nearest even, when stored.
@@ -57,7 +57,7 @@ enum {
 };
 
 /*
- * Flash-attention forward (Section 2 definition; Figure 1 tiling; Section 8
+ * Flash-attention forward ("Motivating Example" definition; Figure 1 tiling; Evaluation's
  * causal GQA workload).  Returns ATTN_OK or a negative ATTN_ERR_* code.
  * causal: 0 = all keys visible, non-zero = bottom-right aligned causal mask.
  */
@@ -95,8 +95,8 @@ int attn_version(void);
 double attn_fwd_flops(int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal);
 
 /*
- * Measurement aid (paper Section 7 measures kernels against the hardware's matrix
- * throughput; the bench reports the published peak AND what this GPU sustains): enqueue
+ * Measurement aid, no part of the method (the bench reports the published matrix peak AND what
+ * this GPU sustains on nothing but matrix instructions): enqueue
  * `blocks` workgroups of 8 wavefronts that each issue 4*iters dense bf16 32x32x16 MFMAs and
  * nothing else.  Returns the FLOPs performed (time it with events on `stream`), or -1.0 on
  * bad arguments / refused launch.  `sink` is DEVICE memory of at least 4 bytes, never
@@ -117,6 +117,16 @@ double attn_mfma_calibration(float *sink, int blocks, int iters, void *stream);
  * Same error behaviour; any other `data` returns -1.0.
  */
 double attn_mfma_calibration_data(float *sink, int blocks, int iters, int data, void *stream);
+
+/*
+ * What the bench prices the kernels against, read from the HIP runtime rather than assumed (measurement aid, no
+ * part of the method): the compute-unit count and the maximum shader clock (kHz) of HIP device `device`, and the
+ * dense bf16 matrix peak that follows from them, cus * 4096 flop per clock * clock, in TFLOP/s (a CDNA4 compute
+ * unit retires 4 x 1024 bf16 multiply-add flops per clock on its four matrix cores).  Any of the three output
+ * pointers may be NULL.  Host memory, host call; touches no stream.  Returns ATTN_OK, ATTN_ERR_BAD_SHAPE for a
+ * negative device index, or ATTN_ERR_LAUNCH if the runtime has no such device.
+ */
+int attn_device_info(int device, int *cus, int *clock_khz, double *bf16_peak_tflops);
 
 #ifdef __cplusplus
 }

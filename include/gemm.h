@@ -1,8 +1,8 @@
 /*
  * gemm.h -- C ABI of the MI355X (gfx950) bf16 matrix product.
  *
- * Operation (the GEMM workload of the paper's Section 8, "GEMM multiplies square BF16
- * matrices with normally distributed entries"; Table 2 lists the optimizations a fast
+ * Operation (the GEMM workload of the paper's Evaluation, "Kernel Performance": products of
+ * square bf16 matrices whose entries are normal draws; Table 2 lists the optimizations a fast
  * kernel for it combines):
  *
  *     C[i,j] = sum_{k < K} A[i,k] * B[k,j]          i < M, j < N

@@ -1,9 +1,9 @@
 /*
  * moe.h -- C ABI of the MI355X (gfx950) fused mixture-of-experts feed-forward in block-quantized FP8.
  *
- * Operation (the fused-MoE workload of the paper's Section 8: "DeepSeek-V3.2's block-quantized
- * FP8 configuration", model dimension H, intermediate dimension I, top-k routing, the experts
- * of one GPU under expert parallelism; Section 8.1 "Fused MoE": tokens are routed through
+ * Operation (the fused-MoE workload of the paper's Evaluation, "Kernel Performance": the block-quantized
+ * FP8 configuration of DeepSeek-V3.2, model dimension H, intermediate dimension I, top-k routing, the experts
+ * of one GPU under expert parallelism; same subsection, "Fused MoE" paragraph: tokens are routed through
  * sorted expert maps, blockwise quantization is preserved, the up-projection intermediates are
  * quantized to FP8 so that both projections run on the FP8 matrix cores).  For every token t and
  * routing slot k whose expert e = ids[t][k] is local (0 <= e < E):

@@ -1,10 +1,10 @@
 """fp64 CPU references -- TEST INFRASTRUCTURE, not the product.
 
-Thin ctypes bindings of ``attn_ref.c`` (the plain definition of Section 2 of the
+Thin ctypes bindings of ``attn_ref.c`` (the plain definition in the "Motivating Example" section of the
 paper: S = Q K^T, P = softmax(S), O = P V, plus scale, GQA, causal mask and LSE as
 the library boundary states them) and of ``gemm_ref.c`` (the bf16 matrix product of
-the paper's GEMM workload, Section 8, as three nested loops) and of ``moe_ref.c`` (the
-block-quantized FP8 mixture-of-experts feed-forward of Section 8, step by step).  Only ``tests/``,
+the paper's GEMM workload, Evaluation / "Kernel Performance", as three nested loops) and of ``moe_ref.c`` (the
+block-quantized FP8 mixture-of-experts feed-forward of the same subsection, step by step).  Only ``tests/``,
 ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import this
 package; the product package never does.  Nothing here touches a GPU or the HIP library.
 """

@@ -7,7 +7,7 @@
  * the smoke check and the bench's cpu_baseline leg may call it.
  *
  * What it computes is the textbook definition the paper starts from
- * (Section 2, "standard attention mechanism"): S = Q K^T, P = softmax(S)
+ * (the attention definition in its "Motivating Example" section): S = Q K^T, P = softmax(S)
  * row-wise, O = P V.  Flash attention is an exact reorganisation of that
  * definition (tiling + online softmax change only the order of the sums), so
  * the definition itself is the oracle.  Extensions the paper's workload and the
@@ -16,7 +16,7 @@
  *     definition has none; callers pass 1/sqrt(D));
  *   - grouped-query attention with contiguous groups, kv head = q head / gqa
  *     (Figure 1: tags of Q use h_q/gqa, K/V tiles are indexed idx_h/gqa);
- *   - the causal mask of the evaluated workload (Section 8, "causal GQA"),
+ *   - the causal mask of the evaluated workload (Evaluation, "Kernel Performance": causal grouped-query attention),
  *     aligned bottom-right: key j is visible to query i iff j <= i + (Sk-Sq);
  *   - the natural-log log-sum-exp of the scaled, visible scores per query row
  *     (not in the paper's kernel; required by the library boundary);

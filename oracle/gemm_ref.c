@@ -6,8 +6,8 @@
  * shared with the GPU path.  Only tests, the smoke check and the bench's
  * cpu_baseline leg may call it.
  *
- * What it computes is the definition of the paper's GEMM workload (Section 8,
- * "GEMM multiplies square BF16 matrices"): C = A B with A [M,K] and B [K,N],
+ * What it computes is the definition of the paper's GEMM workload (Evaluation,
+ * "Kernel Performance": products of square bf16 matrices): C = A B with A [M,K] and B [K,N],
  * c_ij = sum_k a_ik b_kj.  The paper does not say how B lies in memory, so both
  * row-major storages are supported: b_is_nk = 0 reads B as [K,N] (b_kj at
  * b[k*ldb + j]); b_is_nk = 1 reads it as [N,K] (b_kj at b[j*ldb + k]), the layout

@@ -5,9 +5,9 @@
  * SIMD intrinsics, no code shared with the GPU path.  Only tests, the smoke check and the
  * bench's cpu_baseline leg may call it.
  *
- * What it computes is the paper's fused-MoE workload (Section 8: "DeepSeek-V3.2's block-quantized
- * FP8 configuration", model dimension H, intermediate dimension I, top-k routing, the experts of
- * one GPU under expert parallelism; Section 8.1, "Fused MoE": blockwise quantization is
+ * What it computes is the paper's fused-MoE workload (Evaluation, "Kernel Performance": the block-quantized
+ * FP8 configuration of DeepSeek-V3.2, model dimension H, intermediate dimension I, top-k routing, the experts of
+ * one GPU under expert parallelism; same subsection, "Fused MoE" paragraph: blockwise quantization is
  * preserved, tokens are routed through expert maps, the up-projection intermediates are
  * quantized to FP8 before the down projection).  The paper gives no formulas; the steps below
  * are the published block-quantized recipe that configuration names, written out:

@@ -10,7 +10,7 @@ from __future__ import annotations
 import ctypes
 import os
 
-from .build import LIB_PATH, build_library
+from .build import LIB_PATH, build_library, stale_sources
 
 _lib = None
 
@@ -22,13 +22,17 @@ class AttnError(RuntimeError):
 
 
 def load_library(build_if_missing: bool = True):
-    """Load libattn_mi355x.so (building it first only if no built library exists)."""
+    """Load libattn_mi355x.so (building it first only if no built library exists; a library older than its
+    sources is loaded as it is, with a warning: rebuild with `python -m paper_2604_18616_amd.build`)."""
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             if not build_if_missing:
                 raise FileNotFoundError(LIB_PATH)
             build_library()
+        elif stale_sources():
+            import warnings
+            warnings.warn("libattn_mi355x.so is older than %s: rebuild it" % ", ".join(stale_sources()))
         lib = ctypes.CDLL(LIB_PATH)
         i, f, p = ctypes.c_int, ctypes.c_float, ctypes.c_void_p
         lib.attn_fwd.restype = i
@@ -64,6 +68,8 @@ def load_library(build_if_missing: bool = True):
         lib.attn_mfma_calibration.argtypes = [p, i, i, p]
         lib.attn_mfma_calibration_data.restype = ctypes.c_double
         lib.attn_mfma_calibration_data.argtypes = [p, i, i, i, p]
+        lib.attn_device_info.restype = i
+        lib.attn_device_info.argtypes = [i, ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(ctypes.c_double)]
         _lib = lib
     return _lib
 
@@ -74,6 +80,15 @@ def strerror(code: int) -> str:
 
 def version() -> int:
     return load_library().attn_version()
+
+
+def device_info(device: int = 0) -> dict:
+    """Compute units, maximum shader clock and the bf16 matrix peak that follows (attn_device_info)."""
+    cus, khz, peak = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_double(0.0)
+    rc = load_library().attn_device_info(int(device), ctypes.byref(cus), ctypes.byref(khz), ctypes.byref(peak))
+    if rc != 0:
+        raise AttnError(rc, strerror(rc))
+    return {"cus": cus.value, "clock_mhz": khz.value / 1e3, "bf16_peak_tflops_from_props": peak.value}
 
 
 def attn_fwd_flops(B, Hq, Hkv, Sq, Sk, D, causal) -> float:
@@ -116,6 +131,10 @@ def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
         raise ValueError("o must be bfloat16 with q's shape and a contiguous last dimension")
     if lse is None:
         lse = torch.empty((B, Hq, Sq), dtype=torch.float32, device=q.device)
+    if not lse.is_cuda or lse.dtype != torch.float32 or tuple(lse.shape) != (B, Hq, Sq) or not lse.is_contiguous():
+        raise ValueError("lse must be a contiguous float32 CUDA tensor of shape [B, Hq, Sq]")
+    if not o.is_cuda or any(t.device != q.device for t in (k, v, o, lse)):
+        raise ValueError("q, k, v, o, lse must live on one CUDA device")
     if scale is None:
         scale = float(D) ** -0.5
     if stream is None:
@@ -193,10 +212,20 @@ def moe_ffn_fp8(x, ids, wts, w13, s13, w2, s2, y=None, workspace=None, stream=No
     need = lib.moe_ffn_fp8_workspace_bytes(T, H, I, E, K)
     if y is None:
         y = torch.empty((T, H), dtype=torch.bfloat16, device=x.device)
-    if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    if not y.is_cuda or y.dtype != torch.bfloat16 or tuple(y.shape) != (T, H) or not y.is_contiguous():
+        raise ValueError("y must be a contiguous bfloat16 CUDA tensor of shape [T, H]")
+    current = torch.cuda.current_stream(x.device)
     if stream is None:
-        stream = torch.cuda.current_stream(x.device)
+        stream = current
+    if workspace is None:
+        # a temporary is only safe on the stream torch will reuse its memory on: the kernels are still queued
+        # when this function returns
+        if stream.cuda_stream != current.cuda_stream:
+            raise ValueError("pass a workspace when `stream` is not torch's current stream")
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    if (not workspace.is_cuda or workspace.dtype != torch.uint8 or not workspace.is_contiguous()
+            or workspace.numel() < need or workspace.data_ptr() % 256):
+        raise ValueError("workspace must be a contiguous uint8 CUDA tensor of at least moe_workspace_bytes(...) bytes, 256-byte aligned")
     rc = lib.moe_ffn_fp8_ex(x.data_ptr(), ids.data_ptr(), wts.data_ptr(), w13.data_ptr(), s13.data_ptr(), w2.data_ptr(),
                             s2.data_ptr(), y.data_ptr(), T, H, I, E, K, workspace.data_ptr(), workspace.numel(),
                             0, 4, int(row_tile), stream.cuda_stream)

@@ -79,6 +79,18 @@ extern "C" double attn_mfma_calibration_data(float* sink, int blocks, int iters,
     return attn_launch_mfma_calibration(sink, blocks, iters, data, (hipStream_t)stream);
 }
 
+extern "C" int attn_device_info(int device, int* cus, int* clock_khz, double* bf16_peak_tflops) {
+    if (device < 0) return ATTN_ERR_BAD_SHAPE;
+    int n = 0, c = 0, khz = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || device >= n) return ATTN_ERR_LAUNCH;
+    if (hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return ATTN_ERR_LAUNCH;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, device) != hipSuccess) return ATTN_ERR_LAUNCH;
+    if (cus) *cus = c;
+    if (clock_khz) *clock_khz = khz;
+    if (bf16_peak_tflops) *bf16_peak_tflops = (double)c * 4096.0 * (double)khz * 1e3 / 1e12;
+    return ATTN_OK;
+}
+
 extern "C" const char* attn_strerror(int code) {
     switch (code) {
         case ATTN_OK:              return "success";
@@ -96,16 +108,15 @@ extern "C" int attn_version(void) { return ATTN_VERSION; }
 
 extern "C" double attn_fwd_flops(int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal) {
     if (check_dims(B, Hq, Hkv, Sq, Sk, D)) return -1.0;
-    double pairs = 0.0;
+    double pairs;
     if (!causal) {
         pairs = (double)Sq * (double)Sk;
     } else {
-        for (int i = 0; i < Sq; ++i) {
-            long long n = (long long)i + (Sk - Sq) + 1;
-            if (n < 0) n = 0;
-            if (n > Sk) n = Sk;
-            pairs += (double)n;
-        }
+        // row i sees min(Sk, max(0, i + (Sk - Sq) + 1)) keys: an arithmetic series that ends at Sk in row Sq - 1
+        // and starts at row i0 = max(0, Sq - Sk) with first = i0 + (Sk - Sq) + 1 keys
+        const long long i0 = Sq > Sk ? (long long)Sq - Sk : 0;
+        const long long m = (long long)Sq - i0, first = i0 + ((long long)Sk - Sq) + 1;
+        pairs = 0.5 * (double)m * (double)(first + Sk);
     }
     return 4.0 * D * (double)B * (double)Hq * pairs;
 }

@@ -1,5 +1,5 @@
 // Flash-attention forward for gfx950 (MI355X): tiled S^T = K Q^T and O^T += V^T P^T on
-// bf16 MFMA with an fp32 online softmax (paper Section 2 for the method, Figure 1 for the
+// bf16 MFMA with an fp32 online softmax (the paper's "Motivating Example" for the method, Figure 1 for the
 // tiling this re-designs: one wavefront owns 32 query rows, K/V stream through LDS in
 // 64-key tiles, operands swapped so that a softmax row lives in one lane column).
 //
@@ -14,83 +14,14 @@
 
 #include "attn_layout.h"
 #include "attn_launch.h"
+#include "gfx950_prims.h"
 
 namespace {
 
 using namespace attn_layout;
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-
-#define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
+using namespace gfx950;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
-__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
-    typedef __attribute__((ext_vector_type(2))) float f32x2;
-    f32x2 f = {lo, hi};
-    bf16x2 b = __builtin_convertvector(f, bf16x2);
-    return __builtin_bit_cast(unsigned, b);
-}
-
-// Asynchronous 16-byte-per-lane copy HBM -> LDS: lane i's 16 bytes at (base + byte_off)
-// land at LDS address lds_addr + 16*i (verified on gfx950).  Written as inline asm so that
-// the compiler's wait-count pass does not know about the LDS write: given the builtin it
-// puts a full vmcnt(0) wait in front of the next LDS read of ANY buffer, which serialises
-// the prefetch.  Completion is awaited explicitly (s_waitcnt vmcnt) before the barrier
-// that publishes the tile.  M0 is written without the compiler knowing; nothing else in
-// these kernels uses M0 (no LDS-DMA builtins, no indirect register indexing, no GWS).
-__device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_off, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
-}
-
-// The same copy through a buffer resource: lane i's 16 bytes at (resource base + soff + voff) land at
-// lds_addr + 16*i, and a piece that lies past the resource's num_records arrives as zeros (the hardware's
-// out-of-range rule for buffer loads, checked on gfx950 with the LDS form of the instruction): the partial
-// last key tile needs no clamped addresses and no clearing afterwards.
-typedef __attribute__((ext_vector_type(4))) int i32x4;
-__device__ __forceinline__ i32x4 buffer_resource(const void* base, unsigned bytes) {
-    const unsigned long long a = (unsigned long long)base;
-    i32x4 r;
-    r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
-    r[1] = __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu));   // stride 0: a raw buffer
-    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);                              // num_records, in bytes
-    r[3] = 0x00020000;                                                              // 32-bit data format
-    return r;
-}
-__device__ __forceinline__ void dma_buf_to_lds_16B(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
-                 :: "v"(voff), "s"(rsrc), "s"(soff), "s"(lds_addr) : "memory");
-}
-
-// Exchange between lane l and lane l ^ 32.  v_permlane32_swap(a, b) returns
-//   r0 = { a[0..31], b[0..31] },  r1 = { a[32..63], b[32..63] }     (verified on gfx950),
-// so with b = a, (r0, r1) is (value held by the low-half lane, value held by the
-// high-half lane) in every lane.  The two results are copied to scalars before any
-// reinterpretation: a bit cast applied directly to a vector element reads element 0.
-__device__ __forceinline__ void swap_halves(float x, float& lo, float& hi) {
-    const unsigned a = __float_as_uint(x);
-    const u32x2 r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
-    const unsigned r0 = r[0], r1 = r[1];
-    lo = __uint_as_float(r0);
-    hi = __uint_as_float(r1);
-}
-__device__ __forceinline__ float max_across_halves(float x) {
-    float lo, hi;
-    swap_halves(x, lo, hi);
-    return fmaxf(lo, hi);
-}
-__device__ __forceinline__ float sum_across_halves(float x) {
-    float lo, hi;
-    swap_halves(x, lo, hi);
-    return lo + hi;
-}
 
 // Workgroup id -> (batch, query head, query tile).  Workgroups are handed to the 8 XCDs
 // round-robin, and each XCD has its own L2: give every XCD a contiguous range of the
@@ -244,7 +175,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
                 }
         }
 
-        // ---- online softmax (Section 2: "accumulating into O via online softmax")
+        // ---- online softmax ("Motivating Example": O is accumulated tile by tile under a running maximum and sum)
         float mx = s[0][0];
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
@@ -285,7 +216,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
             for (int dblk = 0; dblk < DB; ++dblk) {
                 const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, sV + pv_addr_offset<D>(lane, dblk, kk, 0)));
                 const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, sV + pv_addr_offset<D>(lane, dblk, kk, 1)));
-                typedef __attribute__((ext_vector_type(8))) short s16x8;
                 const s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
                 oacc[dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, oacc[dblk], 0, 0, 0);
             }
@@ -326,7 +256,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
 //   issues the 32 MFMAs of "PV of tile t-1, then QK^T of tile t", the other runs the
 //   softmax VALU work of its current tile, so the matrix pipe and the vector ALU of every
 //   SIMD are busy at the same time (the paper's "pipelining with wavefront
-//   specialization" stage, Section 8.2, re-derived for two symmetric groups).
+//   specialization" stage of the "Ablation Study", Figure 3a, re-derived for two symmetric groups).
 // * No running maximum on the common path: scores are exponentiated against a stale
 //   reference m_ref (set from the true maximum on the wavefront's first tile).  Any
 //   reference gives the same result after normalisation, and bf16 P keeps its relative
@@ -352,16 +282,6 @@ constexpr float kBig = 18446744073709551616.0f;   // 2^64: bound on a partial ro
 constexpr int kPF = ATTN_PF;           // MFMA operands kept in flight from LDS (ring of 4-register fragments)
 constexpr int kSmPrio = ATTN_SM_PRIO;  // wave priority while in the softmax (0 elsewhere).  Measured 0..3: with the max-free
                                        // softmax 0 is 1.2-1.5 % faster than 1-3 at D = 128 (a raised priority helped the older, longer softmax)
-
-template <int V> struct IntC { static constexpr int value = V; };
-// compile-time loop: f(IntC<I>{}) for I = BEGIN .. END-1, everything inlined
-template <int BEGIN, int END, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-    if constexpr (BEGIN < END) {
-        f(IntC<BEGIN>{});
-        static_for<BEGIN + 1, END>(f);
-    }
-}
 
 template <int D, bool CAUSAL, bool RAGGED>
 __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
@@ -508,7 +428,6 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
             constexpr int off = VB * TB + (16 * kk) * (D * 2);
             const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, (size_t)(vaddr[dblk] + off)));
             const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, (size_t)(vaddr[dblk] + off + 8 * (D * 2))));
-            typedef __attribute__((ext_vector_type(8))) short s16x8;
             const s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
             fr[i % kPF] = __builtin_bit_cast(bf16x8, vv);
         } else {
@@ -796,7 +715,6 @@ __global__ __launch_bounds__(512, 1) void mfma_calibration_data_kernel(float* si
         }
     float t = 0.f;
     if constexpr (SHAPE16) {
-        typedef __attribute__((ext_vector_type(4))) float f32x4;
         f32x4 c[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) c[i] = f32x4{0};

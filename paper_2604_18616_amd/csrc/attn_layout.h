@@ -2,7 +2,7 @@
 // compile for both host and device.  The kernels use them for every LDS address
 // and every MFMA lane<->element correspondence; the host tests enumerate them to
 // check the operand-pairing ("tag conformity") and no-collision properties that
-// the paper states as data-flow invariants (Section 4, tag assertions at the two
+// the paper states as data-flow invariants ("The DSL", tag functions and assertions; the assertions at the two
 // MFMA sites of Figure 1), and to count LDS bank conflicts.
 //
 // Tiling (cf. Figure 1: one wavefront owns 32 query rows, K/V stream through LDS

@@ -1,5 +1,5 @@
 // bf16 GEMM for gfx950 (MI355X): C = A B with fp32 accumulation on v_mfma_f32_16x16x32_bf16 or
-// v_mfma_f32_32x32x16_bf16 (the GEMM workload of the paper's Section 8; Table 2 names the ingredients: software
+// v_mfma_f32_32x32x16_bf16 (the GEMM workload of the paper's Evaluation, "Kernel Performance"; Table 2 names the ingredients: software
 // pipelining, MFMA, asynchronous copies, bank-conflict-free LDS layouts, vectorised access,
 // workgroup swizzling, guarded edge handling, explicit scheduling).
 //
@@ -26,50 +26,12 @@
 
 #include "gemm_layout.h"
 #include "gemm_launch.h"
+#include "gfx950_prims.h"
 
 namespace {
 
 using namespace gemm_layout;
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-
-#define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
-
-template <int V> struct IntC { static constexpr int value = V; };
-template <int BEGIN, int END, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-    if constexpr (BEGIN < END) {
-        f(IntC<BEGIN>{});
-        static_for<BEGIN + 1, END>(f);
-    }
-}
-
-// two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
-__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
-    typedef __attribute__((ext_vector_type(2))) float f32x2;
-    f32x2 f = {lo, hi};
-    bf16x2 b = __builtin_convertvector(f, bf16x2);
-    return __builtin_bit_cast(unsigned, b);
-}
-
-// Asynchronous 16-byte-per-lane copy HBM -> LDS: lane i's 16 bytes at (base + byte_off) land
-// at LDS address lds_addr + 16*i.  Inline asm so that the compiler's wait-count pass does not
-// tie every later LDS read to it; completion is awaited explicitly (s_waitcnt vmcnt) before the
-// barrier that publishes the stage.  M0 is written without the compiler knowing; nothing else
-// in these kernels uses M0.
-// The LDS address is lds_addr + IMM with IMM an assembly-time constant: the kernels keep one
-// scalar base per wavefront instead of one scalar per destination.
-template <int IMM>
-__device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_off, unsigned lds_addr) {
-    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(byte_off), "s"(base), "s"(lds_addr), "n"(IMM) : "memory", "scc");
-}
+using namespace gfx950;
 
 // ------------------------------------------------------------------------------------
 // Tiled kernel.  Requires: a, b, c 16-byte aligned; N, K, lda, ldb, ldc multiples of 8;
@@ -86,7 +48,6 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
     constexpr bool MI16 = T::MI == 16;
     // blocks of the wavefront tile per MFMA shape: kRM x kRN result registers sets, kHalfM m-blocks per sub-step (MI16)
     constexpr int kRM = MI16 ? T::kWaveM / 16 : kMB, kRN = MI16 ? gemm_layout::kWaveN / 16 : kNB, kHalfM = kRM / 2;
-    typedef __attribute__((ext_vector_type(4))) float f32x4;
     using Acc = std::conditional_t<MI16, f32x4, f32x16>;
     static_assert(kCopiesA <= kCopiesB, "the copy schedule pairs A with B instructions and ends with the B instructions left over");
     __shared__ __attribute__((aligned(16))) char smem[T::kLdsBytes + 256];   // stages, then the warm-up loads' sink
@@ -312,8 +273,7 @@ __global__ __launch_bounds__(T::kWaves * 64, T::kWaves >= 4 ? T::kPerCU : 1) voi
     const size_t warm_step = (wave == 4 || B_NK) ? (size_t)(kBK * 2) : (size_t)kBK * (size_t)b_rb;
     auto warm = [&](int U) __attribute__((always_inline)) {
         const char* const src = warm_base + (size_t)U * warm_step;
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-                     :: "v"(warm_off), "s"(src), "s"(lds_base + T::kLdsBytes) : "memory");
+        dma_to_lds_4B<0>(src, warm_off, lds_base + T::kLdsBytes);
     };
 
     // vmcnt(n) with lgkmcnt(0): n = copies of the stages that may still be in flight

@@ -1,5 +1,5 @@
 // Fused mixture-of-experts feed-forward in block-quantized FP8 for gfx950 (MI355X): the
-// paper's fused-MoE workload (Section 8; Section 8.1 "Fused MoE": tokens and experts are
+// paper's fused-MoE workload (Evaluation, "Kernel Performance", "Fused MoE" paragraph: tokens and experts are
 // partitioned, tokens reach their experts through sorted maps, blockwise quantization is
 // preserved, the up-projection intermediates are quantized to FP8 so that both projections run
 // on the FP8 matrix cores).
@@ -24,44 +24,13 @@
 
 #include "gemm_layout.h"
 #include "moe_launch.h"
+#include "gfx950_prims.h"
 
 namespace {
 
+using namespace gfx950;
+
 using namespace gemm_layout;   // kt_*: the 128-byte-row swizzled tile of the bf16 GEMM, here 128 e4m3 per row
-
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(8))) int i32x8;
-typedef __attribute__((ext_vector_type(4))) int i32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-#define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
-
-template <int V> struct IntC { static constexpr int value = V; };
-template <int BEGIN, int END, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-    if constexpr (BEGIN < END) {
-        f(IntC<BEGIN>{});
-        static_for<BEGIN + 1, END>(f);
-    }
-}
-
-// Asynchronous 16-byte-per-lane copy HBM -> LDS (lane i's bytes land at lds_addr + IMM + 16 i);
-// inline asm so that the compiler's wait-count pass does not tie later LDS reads to it; awaited
-// explicitly with s_waitcnt vmcnt before the barrier that publishes the stage.
-template <int IMM>
-__device__ __forceinline__ void dma_to_lds_16B(const void* base, unsigned byte_off, unsigned lds_addr) {
-    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(byte_off), "s"(base), "s"(lds_addr), "n"(IMM) : "memory", "scc");
-}
-
-// The same with one dword per lane (lane i's 4 bytes land at lds_addr + IMM + 4 i).
-template <int IMM>
-__device__ __forceinline__ void dma_to_lds_4B(const void* base, unsigned byte_off, unsigned lds_addr) {
-    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-                 :: "v"(byte_off), "s"(base), "s"(lds_addr), "n"(IMM) : "memory", "scc");
-}
 
 // quant128 on four values of a 32-lane group: returns the four e4m3 codes packed little-endian.
 // scale = amax * (1/448) (1 if amax = 0), code = e4m3(clamp(v * (1/scale))): fp32 throughout, a true
@@ -473,7 +442,6 @@ __device__ __forceinline__ void moe_gemm_tile(const MoeParams& p, int e, int row
                         if (c < p.H) {
                             const f32x4 v = {acc[in][mb][4 * g4], acc[in][mb][4 * g4 + 1], acc[in][mb][4 * g4 + 2], acc[in][mb][4 * g4 + 3]};
                             if (dst >= 0) {
-                                typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
                                 const bf16x4 out = {(__bf16)fmaf(w, v[0], 0.0f), (__bf16)fmaf(w, v[1], 0.0f), (__bf16)fmaf(w, v[2], 0.0f), (__bf16)fmaf(w, v[3], 0.0f)};   // as moe_combine: 0 + w * v
                                 *(bf16x4*)(p.y + (size_t)dst * p.H + c) = out;
                             } else {
@@ -554,7 +522,6 @@ __global__ __launch_bounds__(256) void moe_combine(MoeParams p) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) { acc[i] = fmaf(w, a[i], acc[i]); acc[4 + i] = fmaf(w, b[i], acc[4 + i]); }
     }
-    typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
     bf16x8 out;
 #pragma unroll
     for (int i = 0; i < 8; ++i) out[i] = (__bf16)acc[i];

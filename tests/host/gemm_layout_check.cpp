@@ -1,5 +1,5 @@
 // Host-side check of the GEMM kernel's index maps (csrc/gemm_layout.h), compiled with g++ by
-// tests/test_layout_host.py.  The paper's data-flow invariant for GEMM (Section 1: the MFMA
+// tests/test_layout_host.py.  The paper's data-flow invariant for GEMM (Introduction: the MFMA
 // instructions always receive correctly paired elements of A and B whatever the tiling,
 // staging and swizzling in between) recast as plain enumeration over every lane and element:
 //   1. staging is a bijection onto the LDS tile and the copy's lane-contiguous destination

@@ -1,5 +1,5 @@
 // Host-side check of the kernels' index maps (csrc/attn_layout.h), compiled with g++ by
-// tests/test_layout_host.py.  These are the paper's data-flow invariants (Section 4: tag
+// tests/test_layout_host.py.  These are the paper's data-flow invariants ("The DSL", tag functions and assertions: tag
 // assertions at the two MFMA sites of Figure 1; non-conformity of concurrent LDS writers)
 // recast as plain enumeration over every lane, register and step:
 //   1. QK^T conformity: the K element a lane fetches from LDS for MFMA (kb, ks) and the Q element
@@ -12,7 +12,7 @@
 //      every byte of the tile is written; the swizzled chunk position is within the row.
 //   4. Bank model: the K read (16 lanes x 16 B) and the V read (32 lanes x 8 B) touch every
 //      4-byte bank at most once per 256-byte LDS cycle.
-//   5. The bug class of the paper's worked example (Section 5.3: an operand read through the
+//   5. The bug class of the paper's worked example ("Agentic Optimization Harness", the attention example: an operand read through the
 //      staging layout instead of the MFMA view) is detected by check 1 when planted.
 #include <cstdio>
 #include <cstdlib>

@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_header_declares_the_boundary():
     names = declared_functions()
-    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops", "attn_mfma_calibration", "attn_mfma_calibration_data", "attn_fwd_strided"}
+    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops", "attn_mfma_calibration", "attn_mfma_calibration_data", "attn_fwd_strided", "attn_device_info"}
 
 
 def test_library_exports_every_declared_symbol(lib):

@@ -107,7 +107,7 @@ def test_exact_small_integers():
 
 
 @pytest.mark.parametrize("name,tile", [("G1024", 0), ("G1024T", 256), ("G2048", 0), ("G2048T", 0), ("G4096", 0), ("G4096T", 128), ("G4096", 2564), ("G2048T", 2564),
-                                       ("G8192", 0)])
+                                       ("G8192", 0), ("G8192T", 0), ("G16384", 0), ("G16384T", 0)])
 def test_paper_sizes_on_sampled_outputs(name, tile):
     w = I.GEMM_WORKLOADS[name]
     a, b = I.make_ab(w)

@@ -79,4 +79,5 @@ def test_sample_rows():
     assert not np.array_equal(r[0], r[1])
     tiny = I.sample_rows(I.Workload("t", 1, 1, 1, 5, 5, 64, True, 9), 64)
     assert tiny.tolist() == [[0, 1, 2, 3, 4]]
-    assert w.check_rows == 64
+    assert w.check_rows == 0 and I.WORKLOADS["C2"].check_rows == 0        # every row of C2 and C3 is checked
+    assert I.WORKLOADS["C4"].check_rows == 512 and I.WORKLOADS["C5"].check_rows == 256

@@ -1,8 +1,8 @@
 """Pins for the fp64 CPU reference (oracle/attn_ref.c).
 
 Nothing here compares the reference with itself: every test checks it against
-something the definition of attention (paper Section 2: S = QK^T, P = softmax(S),
-O = PV), the causal GQA workload (Section 8) or plain mathematics fixes -- hand
+something the definition of attention (the paper's "Motivating Example": S = QK^T, P = softmax(S),
+O = PV), the causal GQA workload (Evaluation, "Kernel Performance") or plain mathematics fixes -- hand
 worked values, closed forms, invariants, brute force in pure Python, an
 independent library routine on tiny inputs.  Each pin is chosen so that a
 plausible slip (dropped scale, wrong head map, off-by-one mask, transposed

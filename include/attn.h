@@ -53,7 +53,8 @@ enum {
     ATTN_ERR_UNSUPPORTED = -3,  /* D not in {64,128}                                  */
     ATTN_ERR_MISALIGNED  = -4,  /* q/k/v/o not 16-byte aligned, lse not 4-byte aligned */
     ATTN_ERR_BAD_SCALE   = -5,  /* scale is NaN, infinite, zero or negative           */
-    ATTN_ERR_LAUNCH      = -6   /* the HIP runtime refused the launch                 */
+    ATTN_ERR_LAUNCH      = -6,  /* the HIP runtime refused the launch                 */
+    ATTN_ERR_TOO_LARGE   = -7   /* sizes exceed a fixed capacity of the library (moe.h: the library-owned scratch) */
 };
 
 /*

@@ -73,6 +73,25 @@ int moe_ffn_fp8_ex(const void *x, const int *ids, const float *wts,
                    int first_stage, int last_stage, int row_tile, void *stream);
 
 /*
+ * moe_ffn_fp8 for callers that cannot allocate device memory and so have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, arguments, checks and
+ * results as moe_ffn_fp8 (bit for bit: the same kernels run), but the scratch memory is a device array that is
+ * part of the library's code object: MOE_FFN_FP8_STATIC_MAX_BYTES bytes on every GPU the library runs on, held
+ * until the process ends.  The call allocates and frees nothing (no hipMalloc, no hipFree, no allocating library
+ * routine); the first call on a device looks the array's address up once (hipGetSymbolAddress) and keeps it.
+ * Sizes whose moe_ffn_fp8_workspace_bytes(T, H, I, E, KTOP) exceeds MOE_FFN_FP8_STATIC_MAX_BYTES are rejected with
+ * ATTN_ERR_TOO_LARGE and nothing is launched (the paper's configuration, H = 7168, I = 2048, top-4 of 32 local
+ * experts, fits up to T = 1024 tokens).  Every call on one GPU uses that GPU's one array, which keeps whatever the
+ * last call left there; nothing in it needs to start at zero (the first kernel rewrites every table it reads).
+ * Calls that overlap on one GPU -- from two streams or two threads -- race on it: serialise them, or give all
+ * but one a workspace of their own through moe_ffn_fp8.  ATTN_ERR_LAUNCH also covers a failed address lookup.
+ */
+#define MOE_FFN_FP8_STATIC_MAX_BYTES (128u << 20)
+int moe_ffn_fp8_static(const void *x, const int *ids, const float *wts,
+                       const void *w13, const float *s13, const void *w2, const float *s2,
+                       void *y, int T, int H, int I, int E, int KTOP, void *stream);
+
+/*
  * Where the parts of the workspace lie after a call (byte offset, or -1 for unsupported sizes or an
  * unknown part), for debugging and for tests that check the stages of the path one by one.  Rows are
  * in expert order; within an expert their order is not specified.  Parts:

@@ -56,6 +56,8 @@ def load_library(build_if_missing: bool = True):
         lib.moe_ffn_fp8.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, p, ctypes.c_size_t, p]
         lib.moe_ffn_fp8_ex.restype = i
         lib.moe_ffn_fp8_ex.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, p, ctypes.c_size_t, i, i, i, p]
+        lib.moe_ffn_fp8_static.restype = i
+        lib.moe_ffn_fp8_static.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, p]
         lib.moe_ffn_fp8_flops_per_pair.restype = ctypes.c_double
         lib.moe_ffn_fp8_flops_per_pair.argtypes = [i, i]
         lib.attn_strerror.restype = ctypes.c_char_p

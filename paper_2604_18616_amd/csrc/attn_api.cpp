@@ -100,6 +100,7 @@ extern "C" const char* attn_strerror(int code) {
         case ATTN_ERR_MISALIGNED:  return "misaligned pointer (q/k/v/o need 16 bytes, lse 4 bytes)";
         case ATTN_ERR_BAD_SCALE:   return "scale must be finite and > 0";
         case ATTN_ERR_LAUNCH:      return "the HIP runtime refused the kernel launch";
+        case ATTN_ERR_TOO_LARGE:   return "sizes exceed a fixed capacity of the library (moe_ffn_fp8_static: the workspace these sizes need is larger than the library-owned scratch array)";
         default:                   return "unknown attn error code";
     }
 }

@@ -6,6 +6,8 @@
 #include "../../include/moe.h"
 #include "moe_launch.h"
 
+static_assert(kMoeStaticScratchBytes == MOE_FFN_FP8_STATIC_MAX_BYTES, "moe.h states the size of the library-owned scratch array");
+
 static bool sizes_ok(int T, int H, int I, int E, int KTOP) {
     if (T <= 0 || H <= 0 || I <= 0 || E <= 0 || KTOP <= 0) return false;
     if (H % 128 || I % 128 || H > 16384 || I > 16384) return false;
@@ -95,6 +97,19 @@ extern "C" int moe_ffn_fp8(const void* x, const int* ids, const float* wts,
                            void* y, int T, int H, int I, int E, int KTOP,
                            void* workspace, size_t workspace_bytes, void* stream) {
     return moe_ffn_fp8_ex(x, ids, wts, w13, s13, w2, s2, y, T, H, I, E, KTOP, workspace, workspace_bytes, 0, 4, 0, stream);
+}
+
+extern "C" int moe_ffn_fp8_static(const void* x, const int* ids, const float* wts,
+                                  const void* w13, const float* s13, const void* w2, const float* s2,
+                                  void* y, int T, int H, int I, int E, int KTOP, void* stream) {
+    if (!x || !ids || !wts || !w13 || !s13 || !w2 || !s2 || !y) return ATTN_ERR_NULL_PTR;
+    if (!sizes_ok(T, H, I, E, KTOP)) return ATTN_ERR_BAD_SHAPE;
+    size_t off[13];
+    if (moe_workspace_layout(T, H, I, E, KTOP, off) > kMoeStaticScratchBytes) return ATTN_ERR_TOO_LARGE;
+    size_t have = 0;
+    void* const scratch = moe_static_scratch(&have);      // cached per device after the first call; no allocation
+    if (!scratch) return ATTN_ERR_LAUNCH;
+    return moe_ffn_fp8_ex(x, ids, wts, w13, s13, w2, s2, y, T, H, I, E, KTOP, scratch, have, 0, 4, 0, stream);
 }
 
 extern "C" int moe_ffn_fp8_row_tiles(int rows, int row_tile) {

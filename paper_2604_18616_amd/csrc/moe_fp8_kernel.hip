@@ -23,6 +23,8 @@
 #include <stdint.h>
 
 #include "gemm_layout.h"
+#include <mutex>
+
 #include "moe_launch.h"
 #include "gfx950_prims.h"
 
@@ -529,6 +531,31 @@ __global__ __launch_bounds__(256) void moe_combine(MoeParams p) {
 }
 
 }  // namespace
+
+// Scratch memory for callers that cannot allocate (graph capture, tight serving loops): one array per GPU, part
+// of the code object, alive until the process ends.  In host code the array's NAME is only a handle for the
+// symbol lookup below, never an address: every use of its memory goes through the pointer the lookup returned
+// for the device at hand (each GPU holds its own copy at its own address).
+static __device__ __align__(256) unsigned char moe_scratch_array[kMoeStaticScratchBytes];
+
+void* moe_static_scratch(size_t* bytes) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    if (bytes) *bytes = kMoeStaticScratchBytes;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(moe_scratch_array)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptrs[dev] = ptr;
+    }
+    return ptrs[dev];
+}
 
 int moe_launch(const MoeParams& p, int first, int last, hipStream_t stream) {
     auto on = [&](int stage) { return first <= stage && stage <= last; };

@@ -54,3 +54,9 @@ size_t moe_workspace_layout(int T, int H, int I, int E, int KTOP, size_t off[13]
 // Enqueue stages first..last of the path (0 route, 1 quantize x, 2 gate/up, 3 down, 4 combine) on
 // `stream`.  Returns 0, or -1 if a launch was refused.
 int moe_launch(const MoeParams& p, int first, int last, hipStream_t stream);
+
+// Library-owned scratch memory of the allocation-free entry point: the address, on the CURRENT device, of a
+// file-scope device array of *bytes bytes (looked up once per device, then cached); nullptr if the runtime
+// cannot resolve it.  The array is shared by every call on that device.
+constexpr size_t kMoeStaticScratchBytes = (size_t)128 << 20;
+void* moe_static_scratch(size_t* bytes);

@@ -39,7 +39,7 @@ def test_library_exports_every_declared_symbol(lib):
 def test_error_codes_match_header(lib):
     src = open(HEADER).read()
     codes = {m.group(1): int(m.group(2)) for m in re.finditer(r"(ATTN_[A-Z_]+)\s*=\s*(-?\d+)", src)}
-    assert codes["ATTN_OK"] == 0 and len(codes) == 7
+    assert codes["ATTN_OK"] == 0 and len(codes) == 8
     msgs = {c: lib.attn_strerror(c).decode() for c in codes.values()}
     assert len(set(msgs.values())) == len(msgs)            # distinct, non-empty messages
     assert all(msgs.values())
@@ -161,7 +161,7 @@ def test_moe_header_symbols_are_exported(lib):
     src = re.sub(r"/\*.*?\*/", "", open(MOE_HEADER).read(), flags=re.S)
     names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", src)
     assert set(names) == {"moe_ffn_fp8", "moe_ffn_fp8_workspace_bytes", "moe_ffn_fp8_workspace_offset", "moe_ffn_fp8_flops_per_pair",
-                          "moe_ffn_fp8_ex", "moe_ffn_fp8_row_tiles"}
+                          "moe_ffn_fp8_ex", "moe_ffn_fp8_row_tiles", "moe_ffn_fp8_static"}
     for name in names:
         assert hasattr(lib, name), name
     assert lib.moe_ffn_fp8_flops_per_pair(7168, 2048) == 6.0 * 7168 * 2048
@@ -198,6 +198,14 @@ def test_moe_workspace_size_and_argument_errors(lib):
     for kw in (dict(T=0), dict(H=100), dict(I=0), dict(E=0), dict(E=257), dict(K=17), dict(H=16384 + 128), dict(wsb=1024)):
         assert m(**kw) == -2, kw
     assert m(x=A16 + 2) == -4 and m(ws=A16 + 16) == -4 and m(ids=A16 + 1) == -4
+    # the allocation-free variant: same checks, and sizes beyond the library-owned scratch are refused before any HIP call
+    st = lambda T=64, H=256, x=A16, y=A16: lib.moe_ffn_fp8_static(x, A16, A16, A16, A16, A16, A16, y, T, H, 128, 4, 2, None)
+    assert st(x=None) == -1 and st(y=None) == -1 and st(T=0) == -2 and st(H=100) == -2
+    limit = int(re.search(r"MOE_FFN_FP8_STATIC_MAX_BYTES\s*\((\d+)u\s*<<\s*(\d+)\)", open(MOE_HEADER).read()).expand(r"\1 \2").split()[0]) << 20
+    assert limit == 128 << 20
+    assert lib.moe_ffn_fp8_workspace_bytes(1024, 7168, 2048, 32, 4) <= limit < lib.moe_ffn_fp8_workspace_bytes(1032, 7168, 2048, 32, 4)
+    assert lib.moe_ffn_fp8_static(A16, A16, A16, A16, A16, A16, A16, A16, 1032, 7168, 2048, 32, 4, None) == -7
+    assert "scratch" in lib.attn_strerror(-7).decode()
     ex = lambda a, b, rt=0: lib.moe_ffn_fp8_ex(A16, A16, A16, A16, A16, A16, A16, A16, 64, 256, 128, 4, 2, A16, 1 << 30, a, b, rt, None)
     assert ex(-1, 4) == -3 and ex(0, 5) == -3 and ex(3, 2) == -3 and ex(0, 4, 32) == -3 and ex(0, 4, 256) == -3
 

@@ -32,7 +32,17 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
-CPU_SAMPLE_ROWS = {"C1": 0, "C2": 96, "C3": 256, "C4": 48, "C5": 32}   # rows per head for the CPU leg (0 = all)
+# The softmax between the two products is plain vector arithmetic: per score element and lane one v_fma_f32, one
+# v_exp_f32 (issues at half rate: 8 cycles per wavefront, measured), one v_add_f32 for the row sum and half a
+# v_cvt_pk_bf16_f32, i.e. 4.5 issue slots of 4 cycles.  256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles = 614.4 G wavefront
+# instructions per second x 64 lanes / 4.5 slots = 8.74 T score elements per second, each worth 4*D algorithmic
+# FLOPs: the vector-ALU bound of the path, 2237 TFLOP/s at D = 64 (below the matrix peak: it binds) and 4474 at D = 128.
+VALU_SLOTS_PER_SCORE = 4.5
+
+
+def alu_bound_tflops(D: int) -> float:
+    return 256 * 4 * 2.4e9 / 4.0 * 64 / VALU_SLOTS_PER_SCORE * 4.0 * D / 1e12
+CPU_SAMPLE_ROWS = {"C1": 0, "C2": 384, "C3": 768, "C4": 160, "C5": 96}   # rows per head for the CPU leg (0 = all)
 CPU_SAMPLE_DEFAULT = 64
 
 
@@ -381,6 +391,9 @@ def main() -> int:
     flops = lib.attn_fwd_flops(*dims, causal)
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kernel_ms * 1e-3) / 1e12
+    # which roofline binds: the matrix cores, or (at D = 64) the vector ALU that runs the softmax
+    alu_peak = alu_bound_tflops(w.D)
+    bound, peak = ("alu", alu_peak) if alu_peak < PEAK_BF16_TFLOPS else ("mfma", PEAK_BF16_TFLOPS)
 
     # parity of the last measured launch (outputs re-poisoned right before it) + CPU baseline: the fp64 reference on a bounded sample
     cpu = None
@@ -422,8 +435,10 @@ def main() -> int:
                    "flops_per_step": flops, "flop_convention": "algorithmic: 4*D per visible (query,key) pair"},
         "pct_of_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "effective_tflops": w.dense_flops() / (ms_per_step * 1e-3) / 1e12,
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": read_traffic(w.name),
+        "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": read_traffic(w.name),
+                     "mfma_peak": PEAK_BF16_TFLOPS, "mfma_frac": achieved / PEAK_BF16_TFLOPS,
+                     "alu_peak": alu_peak, "alu_frac": achieved / alu_peak,
                      "kernel_ms": kernel_ms, "kernel_ms_single_launches": stats, "mfma_sustained_tflops": mfma_sustained,
                      "mfma_sustained_by_operands": by_operands,
                      "frac_of_sustained": (achieved / mfma_sustained) if mfma_sustained else None},

@@ -82,6 +82,21 @@ int attn_fwd_strided(const void *q, const void *k, const void *v, void *o, float
                      const long long *v_strides, const long long *o_strides,
                      int causal, float scale, void *stream);
 
+/*
+ * attn_fwd with the workgroup shape of the tiled kernel forced, for tuning and for tests that run every shape
+ * through both (the GEMM of the paper's Table 2 lists "tile-size specialization"; attention has the same knob):
+ *   wg_rows = 256: 8 wavefronts x 32 query rows, one workgroup per compute unit, two wavefront groups half a
+ *                  tile apart (the fastest steady state; what long sequences get);
+ *   wg_rows = 128: 4 wavefronts x 32 query rows, two independent workgroups per compute unit (each hides the
+ *                  other's start-up, drain and causal diagonal; what short sequences and small grids get);
+ *   wg_rows = 0:   the library's own choice, i.e. exactly attn_fwd.
+ * Any other value: ATTN_ERR_UNSUPPORTED.  Calls the 128-row kernel with 64-bit addressing serves (Sq <= 64, or a
+ * head of K/V spanning 4 GiB or more) ignore wg_rows.  Everything else as for attn_fwd.
+ */
+int attn_fwd_tile(const void *q, const void *k, const void *v, void *o, float *lse,
+                  int B, int Hq, int Hkv, int Sq, int Sk, int D,
+                  int causal, float scale, int wg_rows, void *stream);
+
 /* Static, never-freed description of a return code of this library. */
 const char *attn_strerror(int code);
 

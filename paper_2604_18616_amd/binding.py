@@ -37,6 +37,8 @@ def load_library(build_if_missing: bool = True):
         i, f, p = ctypes.c_int, ctypes.c_float, ctypes.c_void_p
         lib.attn_fwd.restype = i
         lib.attn_fwd.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, f, p]
+        lib.attn_fwd_tile.restype = i
+        lib.attn_fwd_tile.argtypes = [p, p, p, p, p, i, i, i, i, i, i, i, f, i, p]
         lib.attn_fwd_strided.restype = i
         lib.attn_fwd_strided.argtypes = [p, p, p, p, p, i, i, i, i, i, i, p, p, p, p, i, f, p]
         ll = ctypes.c_longlong
@@ -97,10 +99,15 @@ def attn_fwd_flops(B, Hq, Hkv, Sq, Sk, D, causal) -> float:
     return load_library().attn_fwd_flops(B, Hq, Hkv, Sq, Sk, D, int(bool(causal)))
 
 
-def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, causal, scale, stream_ptr) -> int:
-    """Direct call with integer device addresses; returns the library's status code."""
-    return load_library().attn_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D,
-                                   int(bool(causal)), float(scale), stream_ptr)
+def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, causal, scale, stream_ptr, wg_rows=0) -> int:
+    """Direct call with integer device addresses; returns the library's status code.  wg_rows != 0 goes
+    through attn_fwd_tile (workgroup shape forced: 128 or 256 query rows)."""
+    lib = load_library()
+    if wg_rows:
+        return lib.attn_fwd_tile(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D,
+                                 int(bool(causal)), float(scale), int(wg_rows), stream_ptr)
+    return lib.attn_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D,
+                        int(bool(causal)), float(scale), stream_ptr)
 
 
 def _strides3(t):

@@ -19,8 +19,9 @@ static int check_dims(int B, int Hq, int Hkv, int Sq, int Sk, int D) {
 static int attn_fwd_impl(const void* q, const void* k, const void* v, void* o, float* lse,
                          int B, int Hq, int Hkv, int Sq, int Sk, int D,
                          const long long* qs, const long long* ks, const long long* vs, const long long* os,
-                         int causal, float scale, void* stream) {
+                         int causal, float scale, int wg_rows, void* stream) {
     if (!q || !k || !v || !o) return ATTN_ERR_NULL_PTR;
+    if (wg_rows != 0 && wg_rows != 128 && wg_rows != 256) return ATTN_ERR_UNSUPPORTED;
     if (int rc = check_dims(B, Hq, Hkv, Sq, Sk, D)) return rc;
     if (D != 64 && D != 128) return ATTN_ERR_UNSUPPORTED;
     const long long nQt = ((long long)Sq + 127) / 128;
@@ -47,7 +48,7 @@ static int attn_fwd_impl(const void* q, const void* k, const void* v, void* o, f
     p.nQt = 0; p.nblocks = 0;   // set by the launcher
     p.scale = scale;
     p.scale_log2 = (float)((double)scale * 1.4426950408889634074);
-    return attn_launch(p, D, causal != 0, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+    return attn_launch(p, D, causal != 0, wg_rows, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
 extern "C" int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
@@ -56,7 +57,7 @@ extern "C" int attn_fwd(const void* q, const void* k, const void* v, void* o, fl
     if (int rc = check_dims(B, Hq, Hkv, Sq, Sk, D)) return (q && k && v && o) ? rc : ATTN_ERR_NULL_PTR;
     const long long qs[3] = {(long long)Hq * Sq * D, (long long)Sq * D, D};
     const long long ks[3] = {(long long)Hkv * Sk * D, (long long)Sk * D, D};
-    return attn_fwd_impl(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, qs, ks, ks, qs, causal, scale, stream);
+    return attn_fwd_impl(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, qs, ks, ks, qs, causal, scale, 0, stream);
 }
 
 extern "C" int attn_fwd_strided(const void* q, const void* k, const void* v, void* o, float* lse,
@@ -66,7 +67,16 @@ extern "C" int attn_fwd_strided(const void* q, const void* k, const void* v, voi
                                 int causal, float scale, void* stream) {
     if (!q_strides || !k_strides || !v_strides || !o_strides) return ATTN_ERR_NULL_PTR;
     return attn_fwd_impl(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, q_strides, k_strides, v_strides, o_strides,
-                         causal, scale, stream);
+                         causal, scale, 0, stream);
+}
+
+extern "C" int attn_fwd_tile(const void* q, const void* k, const void* v, void* o, float* lse,
+                             int B, int Hq, int Hkv, int Sq, int Sk, int D,
+                             int causal, float scale, int wg_rows, void* stream) {
+    if (int rc = check_dims(B, Hq, Hkv, Sq, Sk, D)) return (q && k && v && o) ? rc : ATTN_ERR_NULL_PTR;
+    const long long qs[3] = {(long long)Hq * Sq * D, (long long)Sq * D, D};
+    const long long ks[3] = {(long long)Hkv * Sk * D, (long long)Sk * D, D};
+    return attn_fwd_impl(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, qs, ks, ks, qs, causal, scale, wg_rows, stream);
 }
 
 extern "C" double attn_mfma_calibration(float* sink, int blocks, int iters, void* stream) {

@@ -283,26 +283,32 @@ constexpr int kPF = ATTN_PF;           // MFMA operands kept in flight from LDS 
 constexpr int kSmPrio = ATTN_SM_PRIO;  // wave priority while in the softmax (0 elsewhere).  Measured 0..3: with the max-free
                                        // softmax 0 is 1.2-1.5 % faster than 1-3 at D = 128 (a raised priority helped the older, longer softmax)
 
-template <int D, bool CAUSAL, bool RAGGED>
-__global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
+template <int D, bool CAUSAL, bool RAGGED, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void attn_fwd_pingpong(AttnParams p) {
+    static_assert(NW == 8 || NW == 4, "8 wavefronts (256 query rows, one workgroup per CU) or 4 (128 rows, two per CU)");
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;
     constexpr int TB = tile_bytes<D>();
-    constexpr int kBr = 256;
+    constexpr int kBr = NW * kWaveRows;
     constexpr int CPR = D / 8;                  // 16-byte chunks per row
     constexpr int ROWS_PER_DMA = dma_rows_per_inst<D>();   // rows covered by one 1 KB wavefront load
-    constexpr int NDMA = dma_insts_per_wave<D>();          // loads per wavefront per tile and matrix
+    constexpr int NDMA = dma_insts_per_wave<D, NW>();      // loads per wavefront per tile and matrix
     constexpr int NPV = 4 * DB;                 // MFMAs of O^T += V^T P^T per tile
     constexpr int NQK = 2 * KS;                 // MFMAs of S^T = K Q^T per tile
 
-    __shared__ __attribute__((aligned(1024))) char smem[4 * TB];   // K0 K1 V0 V1
-    __shared__ __attribute__((aligned(16))) char smem_o[8 * kWaveRows * D * 2];   // O staging, one 32 x D tile per wavefront
+    // K0 K1 V0 V1, then the O staging area (one 32 x D tile per wavefront).  With 4 wavefronts the staging tiles
+    // lie on K0 K1 instead, which nobody reads after the last workgroup barrier (only PV products of V follow it),
+    // so that two workgroups fit the LDS of a CU.
+    constexpr int kStageBytes = NW * kWaveRows * D * 2;
+    static_assert(NW == 8 || kStageBytes <= 2 * TB, "the staging tiles of the 4-wavefront workgroup lie on K0 K1");
+    __shared__ __attribute__((aligned(1024))) char smem[4 * TB + (NW == 8 ? kStageBytes : 0)];
+    char* const smem_o = NW == 8 ? smem + 4 * TB : smem;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5;
-    const int group = wave >> 2;
+    const int group = NW == 8 ? wave >> 2 : 0;   // 4 wavefronts: all of them MFMA first; the SIMD's other wavefront is another workgroup's
 
     const BlockCoord bc = block_coord<CAUSAL>(blockIdx.x, gridDim.x, p.Hq, p.Hkv, p.nQt);
     const int q0 = bc.qt * kBr;
@@ -332,8 +338,8 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
     // Row pitches in bytes.  The launcher only picks this kernel when a whole head of K and of V
     // spans less than 4 GiB, so every byte offset within a head fits 32 bits.
     const unsigned k_rb = 2u * (unsigned)p.k_ss, v_rb = 2u * (unsigned)p.v_ss;
-    const unsigned kgoff = (unsigned)dma_row<D>(wave, 0, lane) * k_rb + 2u * (unsigned)(dma_src_elem<D, false>(wave, 0, lane) % D);
-    const unsigned vgoff = (unsigned)dma_row<D>(wave, 0, lane) * v_rb + 2u * (unsigned)(dma_src_elem<D, true>(wave, 0, lane) % D);
+    const unsigned kgoff = (unsigned)dma_row<D, NW>(wave, 0, lane) * k_rb + 2u * (unsigned)(dma_src_elem<D, false, NW>(wave, 0, lane) % D);
+    const unsigned vgoff = (unsigned)dma_row<D, NW>(wave, 0, lane) * v_rb + 2u * (unsigned)(dma_src_elem<D, true, NW>(wave, 0, lane) % D);
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(char, smem);
     // The loads of one phase pair, one instruction at a time: slot j < NDMA is part j of V(t),
     // slot j >= NDMA part j - NDMA of K(t+1).  Issued spread over the phase: a burst from all
@@ -350,8 +356,8 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
         v_rsrc = buffer_resource(vh, (unsigned)(Sk - 1) * v_rb + 2u * D);
     }
     auto dma_part = [&](auto is_k, const __bf16* head, unsigned row_bytes, unsigned lane_off, int t, int buf, int n) __attribute__((always_inline)) {
-        const unsigned dst = lds_base + buf * TB + dma_dst_offset<D>(wave, n, 0);
-        const unsigned tile_off = (unsigned)(t * kBc + n * 8 * ROWS_PER_DMA) * row_bytes;   // wavefront-uniform
+        const unsigned dst = lds_base + buf * TB + dma_dst_offset<D, NW>(wave, n, 0);
+        const unsigned tile_off = (unsigned)(t * kBc + n * NW * ROWS_PER_DMA) * row_bytes;   // wavefront-uniform
         if constexpr (RAGGED) dma_buf_to_lds_16B(decltype(is_k)::value ? k_rsrc : v_rsrc, lane_off, tile_off, dst);
         else dma_to_lds_16B((const __bf16*)((const char*)head + tile_off), lane_off, dst);
     };
@@ -503,7 +509,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
             float ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                if (with_dma && dma_t >= 0) {
+                if (NW == 8 && with_dma && dma_t >= 0) {   // group 1 only: 2 * NDMA slots in two halves
                     if (kb == 0) dma_slot(dma_t, 0);
                     if (NDMA == 2) { dma_slot(dma_t, 1 + kb); if (kb == 1) dma_slot(dma_t, 3); }
                     else if (kb == 1) dma_slot(dma_t, 1);
@@ -608,7 +614,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_pingpong(AttnParams p) {
         if (t < nTw) { step(IntC<1>{}, t); ++t; }
         if (t & 1) last(IntC<1>{}, t); else last(IntC<0>{}, t);
         idle_tiles(t + 1);
-    } else {
+    } else if constexpr (NW == 8) {
         loads(0);
         mfma_phase(IntC<0>{}, IntC<0>{}, IntC<0>{}, true, -1);
         end_period(0);
@@ -755,16 +761,31 @@ double attn_launch_mfma_calibration(float* sink, int blocks, int iters, int data
 // Host-side launcher: the only symbol the C-ABI translation unit needs from this file.
 // The ping-pong kernel takes everything except tiny query counts (Sq <= 64: the generic
 // kernel's 128-row workgroups fit two per CU) and ragged key counts whose per-head byte size
-// (or huge row strides) do not fit the 32-bit offsets the tile copies use.
-int attn_launch(AttnParams p, int D, int causal, hipStream_t stream) {
+// (or huge row strides) do not fit the 32-bit offsets the tile copies use.  wg_rows forces its
+// workgroup shape (256 rows by 8 wavefronts, one workgroup per CU; 128 rows by 4, two per CU);
+// 0 picks by attn_auto_rows.
+// Measured on MI355X (TFLOP/s, 128 rows against 256): at D = 64 the 128-row workgroup needs 137 registers and
+// 32 KB of LDS, three of them fit a CU, and it is ahead on every shape tried (+1 % to +42 %: 1087 against 991 on
+// B2 H16 S8192, 617 against 434 on causal B16 H16 S1024); at D = 128 (192 registers, two per CU) every workgroup
+// copies its own K/V tiles, twice the copies per FLOP, and the uncoordinated wavefront pairs lose 6-15 % against the
+// two wavefront groups of the 256-row workgroup, except where 256-row workgroups cannot fill the chip's 256 CUs
+// (64 workgroups: +20 %).
+int attn_auto_rows(const AttnParams& p, int D) {
+    if (D == 64) return 128;
+    const long long wg256 = (long long)p.B * p.Hq * ((p.Sq + 255) / 256);
+    return wg256 <= 128 ? 128 : 256;
+}
+
+int attn_launch(AttnParams p, int D, int causal, int wg_rows, hipStream_t stream) {
     const bool ragged = (p.Sk % 64 != 0);
     const long long kv_ss = p.k_ss > p.v_ss ? p.k_ss : p.v_ss;
     const bool fast = p.Sq > 64 && ((long long)p.Sk + 64) * kv_ss * 2 < (1LL << 32);   // a head of K or V (padded to whole tiles) under 4 GiB
-    const int br = fast ? 256 : 128;
+    const int br = !fast ? 128 : wg_rows ? wg_rows : attn_auto_rows(p, D);
     p.nQt = (p.Sq + br - 1) / br;
     p.nblocks = p.B * p.Hq * p.nQt;
-    const dim3 grid((unsigned)p.nblocks), block(fast ? 512 : 256);
-#define ATTN_LAUNCH_PP(DD, CC, RR) hipLaunchKernelGGL((attn_fwd_pingpong<DD, CC, RR>), grid, block, 0, stream, p)
+    const dim3 grid((unsigned)p.nblocks), block(fast ? br * 2 : 256);
+#define ATTN_LAUNCH_PP(DD, CC, RR) do { if (br == 256) hipLaunchKernelGGL((attn_fwd_pingpong<DD, CC, RR, 8>), grid, block, 0, stream, p); \
+                                        else hipLaunchKernelGGL((attn_fwd_pingpong<DD, CC, RR, 4>), grid, block, 0, stream, p); } while (0)
 #define ATTN_LAUNCH_GEN(DD, CC) hipLaunchKernelGGL((attn_fwd_generic<DD, CC>), grid, block, 0, stream, p)
     if (fast) {
         if (D == 128) {

@@ -18,9 +18,10 @@ struct AttnParams {
     float scale_log2;  // scale * log2(e): scores are exponentiated with exp2
 };
 
-// Enqueue the forward kernel for head dimension D (64 or 128) on `stream`.
+// Enqueue the forward kernel for head dimension D (64 or 128) on `stream`.  wg_rows: query rows per workgroup
+// of the tiled kernel, 256 or 128, or 0 for the launcher's own choice.
 // Returns 0, or -1 if the runtime refused the launch.
-int attn_launch(AttnParams p, int D, int causal, hipStream_t stream);
+int attn_launch(AttnParams p, int D, int causal, int wg_rows, hipStream_t stream);
 
 // Enqueue the pure-MFMA calibration kernel (blocks x 8 wavefronts x iters x 4 MFMAs); returns
 // the FLOPs it performs, or -1 if the launch was refused.  sink: >= 4 bytes of device memory.

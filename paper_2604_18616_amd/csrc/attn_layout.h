@@ -47,21 +47,21 @@ template <int D> ATTN_HD constexpr int tile_bytes() { return kBc * D * 2; }
 template <int D> ATTN_HD constexpr int k_chunk_offset(int row, int chunk) { return row * (D * 2) + ((chunk ^ k_swizzle<D>(row)) * kChunk); }
 template <int D> ATTN_HD constexpr int v_chunk_offset(int row, int chunk) { return row * (D * 2) + ((chunk ^ v_swizzle<D>(row)) * kChunk); }
 
-// ---- direct HBM -> LDS copy of a tile (8 wavefronts) ----------------------------------
+// ---- direct HBM -> LDS copy of a tile (NW wavefronts: 8, or 4 in the 128-row workgroup) ---------
 // The tile is copied by 1 KB wavefront instructions: instruction q writes LDS bytes
 // [1024*q, 1024*(q+1)) lane-contiguously (lane i -> 16 bytes at 1024*q + 16*i), i.e. rows
 // q*R .. q*R+R-1 with R = 1024 / (2*D) rows per instruction.  Wavefront w issues instructions
-// q = w + 8*n.  The swizzle is applied on the source side: lane i fetches the global chunk
-// that belongs at its fixed LDS position.  Rows of n = 1 lie 8*R (a multiple of 16) below
-// those of n = 0, so both swizzles repeat and a lane's source offset for n = 1 is that of
-// n = 0 plus the constant 8*R*D elements.
+// q = w + NW*n.  The swizzle is applied on the source side: lane i fetches the global chunk
+// that belongs at its fixed LDS position.  Rows of part n lie n*NW*R (a multiple of 16) below
+// those of part 0, so both swizzles repeat and a lane's source offset for part n is that of
+// part 0 plus the constant n*NW*R*D elements.
 template <int D> ATTN_HD constexpr int dma_rows_per_inst() { return 1024 / (2 * D); }
-template <int D> ATTN_HD constexpr int dma_insts_per_wave() { return tile_bytes<D>() / 1024 / 8; }
-template <int D> ATTN_HD constexpr int dma_row(int wave, int n, int lane) { return (wave + 8 * n) * dma_rows_per_inst<D>() + lane / (D / 8); }
-template <int D> ATTN_HD constexpr int dma_dst_offset(int wave, int n, int lane) { return (wave + 8 * n) * 1024 + 16 * lane; }
+template <int D, int NW = 8> ATTN_HD constexpr int dma_insts_per_wave() { return tile_bytes<D>() / 1024 / NW; }
+template <int D, int NW = 8> ATTN_HD constexpr int dma_row(int wave, int n, int lane) { return (wave + NW * n) * dma_rows_per_inst<D>() + lane / (D / 8); }
+template <int D, int NW = 8> ATTN_HD constexpr int dma_dst_offset(int wave, int n, int lane) { return (wave + NW * n) * 1024 + 16 * lane; }
 // element offset within the [kBc, D] tile of the 8 bf16 that lane fetches
-template <int D, bool IS_V> ATTN_HD constexpr int dma_src_elem(int wave, int n, int lane) {
-    const int row = dma_row<D>(wave, n, lane);
+template <int D, bool IS_V, int NW = 8> ATTN_HD constexpr int dma_src_elem(int wave, int n, int lane) {
+    const int row = dma_row<D, NW>(wave, n, lane);
     const int pos = lane % (D / 8);
     return row * D + ((pos ^ (IS_V ? v_swizzle<D>(row) : k_swizzle<D>(row))) * 8);
 }

@@ -24,8 +24,9 @@ def from_dev_bf16(t) -> np.ndarray:
     return bf16_bits_to_f32(t.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
 
 
-def run_hip(qb, kb, vb, causal, scale, want_lse=True):
-    """Run the HIP path on bf16 bit arrays; outputs start as NaN so stale memory cannot pass."""
+def run_hip(qb, kb, vb, causal, scale, want_lse=True, wg_rows=0):
+    """Run the HIP path on bf16 bit arrays; outputs start as NaN so stale memory cannot pass.
+    wg_rows: 0 = attn_fwd (the library picks the workgroup shape), 128 / 256 = attn_fwd_tile."""
     import torch
     from paper_2604_18616_amd import binding
     q, k, v = to_dev(qb), to_dev(kb), to_dev(vb)
@@ -35,7 +36,7 @@ def run_hip(qb, kb, vb, causal, scale, want_lse=True):
     _, Hkv, Sk, _ = k.shape
     rc = binding.attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
                               lse.data_ptr() if want_lse else None, B, Hq, Hkv, Sq, Sk, D,
-                              causal, scale, torch.cuda.current_stream().cuda_stream)
+                              causal, scale, torch.cuda.current_stream().cuda_stream, wg_rows=wg_rows)
     assert rc == 0, binding.strerror(rc)
     torch.cuda.synchronize()
     return from_dev_bf16(o), lse.cpu().numpy().astype(np.float64)

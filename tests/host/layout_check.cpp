@@ -28,21 +28,23 @@ static int failures = 0;
 // writes 16-byte chunks: lane-contiguous LDS destination, swizzle applied on the source side.
 template <int D> struct Tile { std::vector<int> row, d; Tile() : row(tile_bytes<D>(), -1), d(tile_bytes<D>(), -1) {} };
 
-template <int D, bool IS_V> Tile<D> stage() {
+template <int D, bool IS_V, int NW = 8> Tile<D> stage() {
     Tile<D> t;
-    constexpr int NDMA = dma_insts_per_wave<D>();
+    constexpr int NDMA = dma_insts_per_wave<D, NW>();
+    static_assert(NDMA * NW * 1024 == tile_bytes<D>(), "the wavefronts' copies tile the buffer");
     std::set<int> written;
-    for (int wave = 0; wave < 8; ++wave)
+    for (int wave = 0; wave < NW; ++wave)
         for (int n = 0; n < NDMA; ++n)
             for (int lane = 0; lane < 64; ++lane) {
-                const int src = dma_src_elem<D, IS_V>(wave, n, lane);          // element offset in the tile
+                const int src = dma_src_elem<D, IS_V, NW>(wave, n, lane);      // element offset in the tile
                 // the kernel derives load n from load 0 plus a constant number of rows
-                const int src0 = dma_src_elem<D, IS_V>(wave, 0, lane);
-                CHECK(src == src0 + n * 8 * dma_rows_per_inst<D>() * D,
+                const int src0 = dma_src_elem<D, IS_V, NW>(wave, 0, lane);
+                CHECK(src == src0 + n * NW * dma_rows_per_inst<D>() * D,
                       "load %d of wave %d lane %d is not load 0 plus a constant", n, wave, lane);
                 const int row = src / D, chunk = (src % D) / 8;
-                CHECK(src % 8 == 0 && row == dma_row<D>(wave, n, lane) && row < kBc, "bad source element %d", src);
-                const int dst = dma_dst_offset<D>(wave, n, lane);
+                const int want_row = dma_row<D, NW>(wave, n, lane);
+                CHECK(src % 8 == 0 && row == want_row && row < kBc, "bad source element %d", src);
+                const int dst = dma_dst_offset<D, NW>(wave, n, lane);
                 const int expect = IS_V ? v_chunk_offset<D>(row, chunk) : k_chunk_offset<D>(row, chunk);
                 CHECK(dst == expect, "copy destination %d != layout offset %d (row %d chunk %d)", dst, expect, row, chunk);
                 for (int b = 0; b < 16; ++b) {
@@ -140,7 +142,15 @@ template <int D> void check_o_stage() {
     }
 }
 
+// The 128-row workgroup copies the same tiles with four wavefronts: same LDS image, every byte once.
+template <int D> void check_four_wave_copy() {
+    const Tile<D> k8 = stage<D, false, 8>(), k4 = stage<D, false, 4>(), v8 = stage<D, true, 8>(), v4 = stage<D, true, 4>();
+    CHECK(k8.row == k4.row && k8.d == k4.d, "K tile image differs between the 8- and the 4-wavefront copy (D=%d)", D);
+    CHECK(v8.row == v4.row && v8.d == v4.d, "V tile image differs between the 8- and the 4-wavefront copy (D=%d)", D);
+}
+
 int main() {
+    check_four_wave_copy<128>(); check_four_wave_copy<64>();
     check_o_stage<128>(); check_o_stage<64>();
     check_qk<128>(false); check_qk<64>(false);
     check_qk<128>(true);  check_qk<64>(true);

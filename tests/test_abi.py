@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_header_declares_the_boundary():
     names = declared_functions()
-    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops", "attn_mfma_calibration", "attn_mfma_calibration_data", "attn_fwd_strided", "attn_device_info"}
+    assert set(names) == {"attn_fwd", "attn_strerror", "attn_version", "attn_fwd_flops", "attn_mfma_calibration", "attn_mfma_calibration_data", "attn_fwd_strided", "attn_device_info", "attn_fwd_tile"}
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -64,6 +64,13 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
         assert call(lib, **kw) == -4, kw
     for s in (0.0, -0.5, math.nan, math.inf, -math.inf):
         assert call(lib, scale=s) == -5, s
+
+
+def test_tile_entry_point_argument_errors(lib):
+    t = lambda rows, q=A16, D=128: lib.attn_fwd_tile(q, A16, A16, A16, A16, 1, 4, 2, 128, 128, D, 1, 0.1, rows, None)
+    for rows in (1, 64, 129, 512, -128):
+        assert t(rows) == -3, rows                         # only 0, 128, 256 name a workgroup shape
+    assert t(128, q=None) == -1 and t(256, D=96) == -3 and t(0, q=A16 + 2) == -4
 
 
 def test_strided_entry_point_argument_errors(lib):

@@ -55,12 +55,15 @@ def test_config_c1_full():
     print(w.name, check(o, lse, o_ref, lse_ref, w.name))
 
 
+@pytest.mark.parametrize("wg_rows", [0, 128, 256])
 @pytest.mark.parametrize("w", SMALL_CASES, ids=lambda w: w.name)
-def test_small_shapes_full_oracle(w):
+def test_small_shapes_full_oracle(w, wg_rows):
+    """Every small shape through attn_fwd (the library picks the workgroup shape) and through attn_fwd_tile with
+    the 128-row (4 wavefronts, several workgroups per CU) and the 256-row (8 wavefronts) workgroup forced."""
     q, k, v = I.make_qkv(w)
-    o, lse = run_hip(q, k, v, w.causal, w.scale)
+    o, lse = run_hip(q, k, v, w.causal, w.scale, wg_rows=wg_rows)
     o_ref, lse_ref = oracle_parallel(q, k, v, w.causal, w.scale)
-    print(w.name, check(o, lse, o_ref, lse_ref, w.name))
+    print(w.name, wg_rows, check(o, lse, o_ref, lse_ref, w.name))
     if w.causal and w.Sq > w.Sk:
         assert (lse[:, :, : w.Sq - w.Sk] == -np.inf).all() and (o[:, :, : w.Sq - w.Sk] == 0).all()
 
@@ -102,9 +105,10 @@ def test_strided_layout_of_the_papers_kernel(D, Sq, Sk, causal):
     assert torch.isnan(pad[..., D:].float()).all()              # padding untouched
 
 
+@pytest.mark.parametrize("wg_rows", [128, 256])
 @pytest.mark.parametrize("direction", ["rising", "falling", "spike"])
 @pytest.mark.parametrize("causal", [False, True])
-def test_scores_far_from_the_first_tile_maximum(direction, causal):
+def test_scores_far_from_the_first_tile_maximum(direction, causal, wg_rows):
     """The kernel exponentiates against a stale reference and only re-bases when a partial sum
     would overflow: drive the scores hundreds of binades away from the first tile's maximum
     (upwards: forces re-basing several times; downwards: everything after the first tiles
@@ -125,9 +129,9 @@ def test_scores_far_from_the_first_tile_maximum(direction, causal):
         k[:, :, 777, :] += 80.0 * u
     qb, kb, vb = (I.f32_to_bf16_bits(x) for x in (q, k, v))
     scale = D ** -0.5
-    o, lse = run_hip(qb, kb, vb, causal, scale)
+    o, lse = run_hip(qb, kb, vb, causal, scale, wg_rows=wg_rows)
     o_ref, lse_ref = oracle_parallel(qb, kb, vb, causal, scale)
-    print(direction, causal, check(o, lse, o_ref, lse_ref, direction))
+    print(direction, causal, wg_rows, check(o, lse, o_ref, lse_ref, direction))
 
 
 def whole_tensor_properties(w, o, lse, v):
@@ -154,8 +158,9 @@ def test_full_size_configs_every_row(name):
     whole_tensor_properties(w, o, lse, v)
 
 
-@pytest.mark.parametrize("name", ["C4", "C5", "P1024", "P4096", "P16384", "N8K"])
-def test_full_size_configs_sampled_rows(name):
+@pytest.mark.parametrize("name,wg_rows", [("C4", 0), ("C5", 0), ("P1024", 0), ("P4096", 0), ("P16384", 0), ("N8K", 0),
+                                          ("C4", 256), ("C5", 128), ("P1024", 128)])
+def test_full_size_configs_sampled_rows(name, wg_rows):
     """C4 (512 rows per head) and C5 (256), as the benchmark definition states, and the shapes of the paper's own
     attention workload (Evaluation, "Kernel Performance"; x-axis of Figure 3a: batch 16, 8 query heads on 1 kv
     head, d = 128, causal, sequence 1024 / 4096 / 16384) plus the long non-causal case, 64 rows per head: the
@@ -164,7 +169,7 @@ def test_full_size_configs_sampled_rows(name):
     w = I.WORKLOADS[name]
     q, k, v = I.make_qkv(w)
     rows = I.sample_rows(w, w.check_rows)
-    o, lse = run_hip(q, k, v, w.causal, w.scale)
+    o, lse = run_hip(q, k, v, w.causal, w.scale, wg_rows=wg_rows)   # 0: the shape the bench times; else the other one
     o_ref, lse_ref = oracle_parallel(q, k, v, w.causal, w.scale, rows=rows)
     idx = rows.reshape(w.B, w.Hq, -1)
     o_s = np.take_along_axis(o, idx[..., None], axis=2)

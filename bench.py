@@ -232,6 +232,7 @@ def bench_gemm(args, torch, lib, binding, I, dev) -> int:
 
 
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E (published)
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense FP8 MFMA peak (published)
 
 
 def bench_moe(args, torch, lib, binding, I, dev) -> int:
@@ -272,6 +273,11 @@ def bench_moe(args, torch, lib, binding, I, dev) -> int:
     # algorithmic bytes of the gate/up kernel: the used experts' w13 once, one quantized row in and one out per pair, scales
     up_bytes = used * (2.0 * w.I * w.H + 4.0 * (2 * w.I // 128) * (w.H // 128)) + pairs * (w.H + 4.0 * w.H / 128 + w.I + 4.0 * w.I / 128)
     achieved = up_bytes / (up_ms * 1e-3) / 1e9
+    # which roofline binds the gate/up kernel at this size: HBM (its algorithmic bytes at 8 TB/s) or the FP8 matrix
+    # cores (4*I*H FLOPs per routed pair at the dense FP8 peak); both fractions are reported
+    up_flops = 4.0 * w.I * w.H * pairs
+    t_hbm, t_mfma = up_bytes / (PEAK_HBM_GBS * 1e9), up_flops / (PEAK_FP8_TFLOPS * 1e12)
+    up_tflops = up_flops / (up_ms * 1e-3) / 1e12
 
     cpu = parity = None
     if not args.no_cpu_baseline:
@@ -298,7 +304,10 @@ def bench_moe(args, torch, lib, binding, I, dev) -> int:
         "config": {"workload": "%s: T=%d tokens, H=%d, I=%d, top-%d of %d experts, %d local, seed %d: %d local pairs on %d experts"
                                % (w.name, w.T, w.H, w.I, w.KTOP, w.E * w.EP, w.E, w.seed, pairs, used),
                    "flops_per_step": flops, "flop_convention": "6*H*I per routed (token, local expert) pair"},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
+        "roofline": ({"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS}
+                     if t_hbm >= t_mfma else
+                     {"bound": "mfma", "achieved": up_tflops, "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": up_tflops / PEAK_FP8_TFLOPS}) | {
+                     "hbm_frac": achieved / PEAK_HBM_GBS, "mfma_frac": up_tflops / PEAK_FP8_TFLOPS,
                      "traffic": read_traffic(w.name, "moe_gemm_up"), "kernel": "moe_gemm<UP> (stage 2 of 5)", "kernel_ms": up_ms,
                      "algorithmic_bytes": up_bytes, "path_ms": path_ms,
                      "path_algorithmic_gbs": w.bytes(ids) / (path_ms * 1e-3) / 1e9},

@@ -45,10 +45,11 @@ static int attn_fwd_impl(const void* q, const void* k, const void* v, void* o, f
     p.k_sb = ks[0]; p.k_sh = ks[1]; p.k_ss = ks[2];
     p.v_sb = vs[0]; p.v_sh = vs[1]; p.v_ss = vs[2];
     p.o_sb = os[0]; p.o_sh = os[1]; p.o_ss = os[2];
-    p.nQt = 0; p.nblocks = 0;   // set by the launcher
+    p.nQt = 0; p.nblocks = 0; p.hpw = 1; p.hpw_log2 = 0;   // set by the launcher
     p.scale = scale;
     p.scale_log2 = (float)((double)scale * 1.4426950408889634074);
-    return attn_launch(p, D, causal != 0, wg_rows, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+    const int rc = attn_launch(p, D, causal != 0, wg_rows, (hipStream_t)stream);
+    return rc == 0 ? ATTN_OK : rc == -2 ? ATTN_ERR_BAD_SHAPE : ATTN_ERR_LAUNCH;
 }
 
 extern "C" int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,

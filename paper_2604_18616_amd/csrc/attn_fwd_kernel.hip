@@ -23,21 +23,24 @@ using namespace gfx950;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Workgroup id -> (batch, query head, query tile).  Workgroups are handed to the 8 XCDs
+// Workgroup id -> (batch, first query head, query tile).  Workgroups are handed to the 8 XCDs
 // round-robin, and each XCD has its own L2: give every XCD a contiguous range of the
 // logical order, in which all query tiles of the gqa heads that share one kv head are
 // neighbours, so that one XCD's resident workgroups stream the same K/V through its L2.
 // Causal: heavy (late) query tiles first.
+// hpw = query heads of one kv head that a workgroup covers side by side (1 for the generic kernel): its
+// wavefronts then take the same row range of hpw heads instead of hpw times as many rows of one head.
 struct BlockCoord { int b, hq, hk, qt; };
 template <bool CAUSAL>
-__device__ __forceinline__ BlockCoord block_coord(int bid, int nblocks, int Hq, int Hkv, int nQt) {
+__device__ __forceinline__ BlockCoord block_coord(int bid, int nblocks, int Hq, int Hkv, int nQt, int hpw) {
     const int g = Hq / Hkv;
+    const int gg = g / hpw;                       // head groups per kv head
     const int per_xcd = nblocks >> 3;
     const int logical = (bid < per_xcd * 8) ? (bid & 7) * per_xcd + (bid >> 3) : bid;
-    const int W = g * nQt;
+    const int W = gg * nQt;
     const int pair = logical / W, rem = logical - pair * W;
-    int ord = rem / g;
-    const int hin = rem - ord * g;
+    int ord = rem / gg;
+    const int hin = rem - ord * gg;
     // Causal tiles go heaviest first.  If one kv head's workgroups are more than an XCD's share (many query
     // heads per kv head), a heavy-first order would give one XCD the long tiles and the next the short ones:
     // then the order alternates longest, shortest, second longest, ... so that every stretch of it is balanced.
@@ -45,7 +48,7 @@ __device__ __forceinline__ BlockCoord block_coord(int bid, int nblocks, int Hq, 
     BlockCoord c;
     c.b = pair / Hkv;
     c.hk = pair - c.b * Hkv;
-    c.hq = c.hk * g + hin;
+    c.hq = c.hk * g + hin * hpw;
     c.qt = CAUSAL ? nQt - 1 - ord : ord;
     return c;
 }
@@ -72,7 +75,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_generic(AttnParams p) {
     const int wave = tid >> 6;
     const int half = lane >> 5;
 
-    const BlockCoord bc = block_coord<CAUSAL>(blockIdx.x, gridDim.x, p.Hq, p.Hkv, p.nQt);
+    const BlockCoord bc = block_coord<CAUSAL>(blockIdx.x, gridDim.x, p.Hq, p.Hkv, p.nQt, 1);
     const int q0 = bc.qt * kBr;
     const int Sq = p.Sq, Sk = p.Sk;
     const int shift = Sk - Sq;                 // causal: key j visible to query i iff j <= i + shift
@@ -310,20 +313,27 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void attn_fwd_pingpong(At
     const int half = lane >> 5;
     const int group = NW == 8 ? wave >> 2 : 0;   // 4 wavefronts: all of them MFMA first; the SIMD's other wavefront is another workgroup's
 
-    const BlockCoord bc = block_coord<CAUSAL>(blockIdx.x, gridDim.x, p.Hq, p.Hkv, p.nQt);
-    const int q0 = bc.qt * kBr;
+    // Grouped-query heads side by side: the workgroup covers rows [q0, q0 + wph * 32) of p.hpw query heads that
+    // share one kv head (wph = NW / hpw wavefronts each) instead of NW * 32 rows of one head.  All its wavefronts
+    // then need nearly the same key tiles under a causal mask -- none drops out along the diagonal, which is one or
+    // two tiles wide instead of four -- and fewer pairs above the diagonal are computed and thrown away.
+    const BlockCoord bc = block_coord<CAUSAL>(blockIdx.x, gridDim.x, p.Hq, p.Hkv, p.nQt, p.hpw);
+    const int wph = NW >> p.hpw_log2;
+    const int hsel = wave >> (NW == 8 ? 3 - p.hpw_log2 : 2 - p.hpw_log2), rblk = wave & (wph - 1);
+    const int hq = bc.hq + hsel;               // this wavefront's query head
+    const int q0 = bc.qt * (wph * kWaveRows);
     const int Sq = p.Sq, Sk = p.Sk;
     const int shift = Sk - Sq;
 
-    const __bf16* qh = p.q + bc.b * p.q_sb + bc.hq * p.q_sh;
+    const __bf16* qh = p.q + bc.b * p.q_sb + hq * p.q_sh;
     const __bf16* kh = p.k + bc.b * p.k_sb + bc.hk * p.k_sh;
     const __bf16* vh = p.v + bc.b * p.v_sb + bc.hk * p.v_sh;
 
     // tiles visited by the workgroup / by this wavefront
     int nT, nTw;
-    const int wrow0 = q0 + wave * kWaveRows;
+    const int wrow0 = q0 + rblk * kWaveRows;
     {
-        const int q_last = min(q0 + kBr - 1, Sq - 1);
+        const int q_last = min(q0 + wph * kWaveRows - 1, Sq - 1);
         const int lim_max = CAUSAL ? min(Sk - 1, q_last + shift) : Sk - 1;
         nT = lim_max < 0 ? 0 : lim_max / kBc + 1;
         const int wlim_max = CAUSAL ? min(Sk - 1, min(wrow0 + kWaveRows - 1, Sq - 1) + shift) : Sk - 1;
@@ -654,7 +664,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void attn_fwd_pingpong(At
                 w[1] = pack_bf16x2(oacc[dblk][4 * g4 + 2] * inv, oacc[dblk][4 * g4 + 3] * inv);
                 *(u32x2*)(stage + o_stage_offset<D>(row, o_d(lane, dblk, 4 * g4))) = w;
             }
-        __bf16* const otile = p.o + bc.b * p.o_sb + bc.hq * p.o_sh + (long long)wrow0 * p.o_ss;
+        __bf16* const otile = p.o + bc.b * p.o_sb + hq * p.o_sh + (long long)wrow0 * p.o_ss;
         constexpr int ROWS_PER_ST = 64 / CPR;
 #pragma unroll
         for (int j = 0; j < kWaveRows / ROWS_PER_ST; ++j) {
@@ -666,7 +676,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void attn_fwd_pingpong(At
     }
     if (qi < Sq && p.lse != nullptr && half == 0) {
         const float v = l_tot > 0.f ? m_ref * p.scale + logf(l_tot) : -INFINITY;
-        p.lse[((size_t)bc.b * p.Hq + bc.hq) * (size_t)Sq + qi] = v;
+        p.lse[((size_t)bc.b * p.Hq + hq) * (size_t)Sq + qi] = v;
     }
 }
 
@@ -781,8 +791,18 @@ int attn_launch(AttnParams p, int D, int causal, int wg_rows, hipStream_t stream
     const long long kv_ss = p.k_ss > p.v_ss ? p.k_ss : p.v_ss;
     const bool fast = p.Sq > 64 && ((long long)p.Sk + 64) * kv_ss * 2 < (1LL << 32);   // a head of K or V (padded to whole tiles) under 4 GiB
     const int br = !fast ? 128 : wg_rows ? wg_rows : attn_auto_rows(p, D);
-    p.nQt = (p.Sq + br - 1) / br;
-    p.nblocks = p.B * p.Hq * p.nQt;
+    // heads of one kv head side by side in a workgroup of the tiled kernel: the largest power of two that divides
+    // the group size and leaves every head at least one wavefront (32 rows)
+    p.hpw = 1; p.hpw_log2 = 0;
+    if (fast) {
+        const int g = p.Hq / p.Hkv, nw = br / 32;
+        while (p.hpw * 2 <= nw && g % (p.hpw * 2) == 0) { p.hpw *= 2; ++p.hpw_log2; }
+    }
+    const int rows_per_head = br / p.hpw;
+    p.nQt = (p.Sq + rows_per_head - 1) / rows_per_head;
+    const long long nblocks = (long long)p.B * (p.Hq / p.hpw) * p.nQt;
+    if (nblocks >= (1LL << 31)) return -2;
+    p.nblocks = (int)nblocks;
     const dim3 grid((unsigned)p.nblocks), block(fast ? br * 2 : 256);
 #define ATTN_LAUNCH_PP(DD, CC, RR) do { if (br == 256) hipLaunchKernelGGL((attn_fwd_pingpong<DD, CC, RR, 8>), grid, block, 0, stream, p); \
                                         else hipLaunchKernelGGL((attn_fwd_pingpong<DD, CC, RR, 4>), grid, block, 0, stream, p); } while (0)

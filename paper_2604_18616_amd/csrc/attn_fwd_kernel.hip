@@ -23,36 +23,6 @@ using namespace gfx950;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Workgroup id -> (batch, first query head, query tile).  Workgroups are handed to the 8 XCDs
-// round-robin, and each XCD has its own L2: give every XCD a contiguous range of the
-// logical order, in which all query tiles of the gqa heads that share one kv head are
-// neighbours, so that one XCD's resident workgroups stream the same K/V through its L2.
-// Causal: heavy (late) query tiles first.
-// hpw = query heads of one kv head that a workgroup covers side by side (1 for the generic kernel): its
-// wavefronts then take the same row range of hpw heads instead of hpw times as many rows of one head.
-struct BlockCoord { int b, hq, hk, qt; };
-template <bool CAUSAL>
-__device__ __forceinline__ BlockCoord block_coord(int bid, int nblocks, int Hq, int Hkv, int nQt, int hpw) {
-    const int g = Hq / Hkv;
-    const int gg = g / hpw;                       // head groups per kv head
-    const int per_xcd = nblocks >> 3;
-    const int logical = (bid < per_xcd * 8) ? (bid & 7) * per_xcd + (bid >> 3) : bid;
-    const int W = gg * nQt;
-    const int pair = logical / W, rem = logical - pair * W;
-    int ord = rem / gg;
-    const int hin = rem - ord * gg;
-    // Causal tiles go heaviest first.  If one kv head's workgroups are more than an XCD's share (many query
-    // heads per kv head), a heavy-first order would give one XCD the long tiles and the next the short ones:
-    // then the order alternates longest, shortest, second longest, ... so that every stretch of it is balanced.
-    if (CAUSAL && W > per_xcd && per_xcd > 0) ord = (ord & 1) ? nQt - 1 - (ord >> 1) : (ord >> 1);
-    BlockCoord c;
-    c.b = pair / Hkv;
-    c.hk = pair - c.b * Hkv;
-    c.hq = c.hk * g + hin * hpw;
-    c.qt = CAUSAL ? nQt - 1 - ord : ord;
-    return c;
-}
-
 // ------------------------------------------------------------------------------------
 // Generic kernel: any Sq, Sk >= 1.  256 threads = 4 wavefronts x 32 query rows (Br = 128),
 // Bc = 64.  K/V tiles are prefetched global -> registers (128-bit loads, zero fill past

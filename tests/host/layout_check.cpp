@@ -12,6 +12,8 @@
 //      every byte of the tile is written; the swizzled chunk position is within the row.
 //   4. Bank model: the K read (16 lanes x 16 B) and the V read (32 lanes x 8 B) touch every
 //      4-byte bank at most once per 256-byte LDS cycle.
+//   6. The workgroup-id -> block map is a bijection onto (batch, head group, query tile), keeps an XCD on one kv
+//      head at a time and orders causal tiles heaviest first.
 //   5. The bug class of the paper's worked example ("Agentic Optimization Harness", the attention example: an operand read through the
 //      staging layout instead of the MFMA view) is detected by check 1 when planted.
 #include <cstdio>
@@ -149,7 +151,42 @@ template <int D> void check_four_wave_copy() {
     CHECK(v8.row == v4.row && v8.d == v4.d, "V tile image differs between the 8- and the 4-wavefront copy (D=%d)", D);
 }
 
+// Workgroup id -> block: every (batch, head group, query tile) of the problem is taken by exactly one workgroup, the
+// kv head is the one the query heads read, every XCD (workgroup id % 8) gets a contiguous stretch of the logical order
+// in which the head groups and query tiles of one kv head are neighbours, and causal tiles come heaviest first within
+// a kv head (or alternate longest / shortest when one kv head's blocks exceed an XCD's share).
+template <bool CAUSAL> void check_block_coord(int B, int Hq, int Hkv, int nQt, int hpw) {
+    const int g = Hq / Hkv, gg = g / hpw, nblocks = B * (Hq / hpw) * nQt;
+    std::set<long long> seen;
+    std::vector<int> prev_qt(8, -1), prev_pair(8, -1);
+    for (int bid = 0; bid < nblocks; ++bid) {
+        const BlockCoord c = block_coord<CAUSAL>(bid, nblocks, Hq, Hkv, nQt, hpw);
+        CHECK(c.b >= 0 && c.b < B && c.hk >= 0 && c.hk < Hkv && c.qt >= 0 && c.qt < nQt, "block %d out of range (b %d hk %d qt %d)", bid, c.b, c.hk, c.qt);
+        CHECK(c.hq % hpw == 0 && c.hq / g == c.hk && c.hq + hpw <= Hq, "block %d: heads %d..%d do not read kv head %d", bid, c.hq, c.hq + hpw - 1, c.hk);
+        const long long key = ((long long)c.b * Hq + c.hq) * nQt + c.qt;
+        CHECK(!seen.count(key), "block (b %d, hq %d, qt %d) taken twice", c.b, c.hq, c.qt);
+        seen.insert(key);
+        // within an XCD's share (full shares only), consecutive workgroups stay on a kv head until it is exhausted
+        const int per_xcd = nblocks >> 3, x = bid & 7;
+        if (bid < per_xcd * 8) {
+            const int pair = c.b * Hkv + c.hk;
+            CHECK(pair >= prev_pair[x], "XCD %d goes back from (b, hk) pair %d to %d", x, prev_pair[x], pair);
+            if (CAUSAL && pair == prev_pair[x] && gg * nQt <= per_xcd) CHECK(c.qt <= prev_qt[x], "XCD %d: causal tile %d after %d is not heaviest first", x, c.qt, prev_qt[x]);
+            prev_pair[x] = pair; prev_qt[x] = c.qt;
+        }
+    }
+    CHECK((int)seen.size() == nblocks, "%zu of %d blocks covered", seen.size(), nblocks);
+}
+
 int main() {
+    for (int hpw : {1, 2, 4, 8}) {
+        check_block_coord<true>(4, 32, 8, 64, hpw <= 4 ? hpw : 4);                             // the headline shape and its packings
+        check_block_coord<false>(2, 16, 16, 32, 1);
+        check_block_coord<true>(16, 8, 1, 32, hpw);                                            // 8 query heads on one kv head
+        check_block_coord<true>(1, 32, 1, 33, hpw);                                            // one kv head larger than an XCD's share, odd tile count
+        check_block_coord<false>(3, 6, 2, 5, 1);                                               // not a multiple of 8 workgroups
+        check_block_coord<true>(1, 2, 2, 1, 1);                                                // fewer than 8 workgroups
+    }
     check_four_wave_copy<128>(); check_four_wave_copy<64>();
     check_o_stage<128>(); check_o_stage<64>();
     check_qk<128>(false); check_qk<64>(false);
